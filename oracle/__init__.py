@@ -1,0 +1,137 @@
+"""fp64 CPU oracle for Flash Decode -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+
+Thin ctypes access to ``fd_oracle.c`` (plain C, fp64, two-pass softmax
+attention + LSE, and the online-softmax Combine of Algorithm 4, Part 2).
+Only ``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s cpu_baseline
+leg may import this package; the HIP library and its Python binding never do,
+and this package imports nothing from them.
+
+Inputs are raw bf16 bit patterns held in ``numpy.uint16`` arrays (numpy has no
+bf16 type); the C code widens them exactly to fp64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fd_oracle.c")
+_LIB = os.path.join(_HERE, "libfd_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile fd_oracle.c with gcc into oracle/libfd_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        lib.fd_oracle_decode.restype = ctypes.c_int
+        lib.fd_oracle_decode.argtypes = [u16p, u16p, u16p, i32p, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                         ctypes.c_double, ctypes.c_int, f64p, f64p]
+        lib.fd_oracle_partial.restype = ctypes.c_int
+        lib.fd_oracle_partial.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int,
+                                          ctypes.c_int, ctypes.c_int64, ctypes.c_double,
+                                          ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                          ctypes.c_int64, f64p, f64p]
+        lib.fd_oracle_merge.restype = ctypes.c_int
+        lib.fd_oracle_merge.argtypes = [f64p, f64p, ctypes.c_int, ctypes.c_int, f64p, f64p]
+        lib.fd_oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _u16(a: np.ndarray, ndim: int, name: str) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint16 or a.ndim != ndim:
+        raise TypeError(f"{name}: expected uint16 (bf16 bits) array with {ndim} dims, "
+                        f"got {a.dtype} with {a.ndim}")
+    return a
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def max_threads() -> int:
+    return int(_load().fd_oracle_max_threads())
+
+
+def decode(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lens: np.ndarray,
+           scale: float = 0.0, n_threads: int = 0):
+    """softmax(scale * q K^T) V and LSE for every (b, h).
+
+    q [B,Hq,D], k/v [B,Hkv,S_max,D] as bf16 bits; seq_lens [B] int32.
+    Returns (out [B,Hq,D] float64, lse [B,Hq] float64, natural log).
+    """
+    q = _u16(q, 3, "q")
+    k = _u16(k, 4, "k")
+    v = _u16(v, 4, "v")
+    B, Hq, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[3] != D:
+        raise ValueError(f"shape mismatch: q {q.shape}, k {k.shape}, v {v.shape}")
+    Hkv, S_max = k.shape[1], k.shape[2]
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if sl.shape != (B,):
+        raise ValueError("seq_lens must have shape [B]")
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    rc = _load().fd_oracle_decode(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16),
+                                  _ptr(v, ctypes.c_uint16), _ptr(sl, ctypes.c_int32),
+                                  B, Hq, Hkv, D, S_max, float(scale), int(n_threads),
+                                  _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("fd_oracle_decode rejected its arguments")
+    return out, lse
+
+
+def partial(q: np.ndarray, k: np.ndarray, v: np.ndarray, b: int, h: int, j0: int, j1: int,
+            scale: float = 0.0):
+    """Attention of query row (b, h) over keys [j0, j1) only: (o [D], lse)."""
+    q = _u16(q, 3, "q")
+    k = _u16(k, 4, "k")
+    v = _u16(v, 4, "v")
+    _, Hq, D = q.shape
+    Hkv, S_max = k.shape[1], k.shape[2]
+    if not (0 <= b < q.shape[0]) or k.shape != v.shape or k.shape[0] != q.shape[0]:
+        raise ValueError("bad batch index or shapes")
+    o = np.empty(D, dtype=np.float64)
+    lse = np.empty(1, dtype=np.float64)
+    rc = _load().fd_oracle_partial(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16),
+                                   _ptr(v, ctypes.c_uint16), Hq, Hkv, D, S_max, float(scale),
+                                   int(b), int(h), int(j0), int(j1),
+                                   _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("fd_oracle_partial rejected its arguments")
+    return o, float(lse[0])
+
+
+def merge(part_o: np.ndarray, part_lse: np.ndarray):
+    """Combine n normalised partials: part_o [n, D], part_lse [n] -> (o [D], lse)."""
+    po = np.ascontiguousarray(part_o, dtype=np.float64)
+    pl = np.ascontiguousarray(part_lse, dtype=np.float64)
+    if po.ndim != 2 or pl.shape != (po.shape[0],):
+        raise ValueError("part_o must be [n, D] and part_lse [n]")
+    n, D = po.shape
+    o = np.empty(D, dtype=np.float64)
+    lse = np.empty(1, dtype=np.float64)
+    rc = _load().fd_oracle_merge(_ptr(po, ctypes.c_double), _ptr(pl, ctypes.c_double), n, D,
+                                 _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("fd_oracle_merge rejected its arguments")
+    return o, float(lse[0])
