@@ -1,0 +1,165 @@
+/*
+ * fd.h -- C ABI of the MI355X (gfx950) Flash Decode library, libfd.so.
+ *
+ * Flash Decode = attention of ONE query token per sequence against a bf16 KV
+ * cache.  The KV range of each sequence is cut into splits; every split is
+ * attended independently (partial output + log-sum-exp), and the partials are
+ * merged by the online-softmax Combine.  This is the single-GPU form of the
+ * paper's Distributed Flash Decode (Section 4.2, Algorithm 4): a KV split plays
+ * the role of a rank's KV shard, the partial buffer the role of the inbox, and
+ * a per-(batch, KV head) arrival counter the role of the signal flags.
+ *
+ *   fd_decode      "fused": ONE persistent kernel.  The workgroup that finishes
+ *                  the last split of a (batch, KV head) tile, detected with an
+ *                  atomic counter, merges that tile's partials on the spot
+ *                  (Section 4.2.5 "Fused Kernels"; Algorithm 4 Part 1 + Part 2
+ *                  without the global barrier and without the second launch).
+ *   fd_decode_bsp  bulk-synchronous baseline (Section 4.2.2): kernel 1 writes
+ *                  all partials, kernel 2 merges them; stream order is the
+ *                  global barrier.  Same arithmetic, bitwise-identical results.
+ *
+ * All tensor pointers are DEVICE pointers owned by the caller; the library
+ * owns only the handle's workspace.  Calls are asynchronous on the caller's
+ * stream: they never synchronise and never allocate.  Calls that share a
+ * handle must be issued on one stream (they share the workspace).
+ *
+ * Every function returns FD_OK (0) or a negative FD_ERR_* code; the text of the
+ * last error of the calling thread is available from fd_last_error().  No
+ * exception crosses this boundary.  Argument checks happen on the host before
+ * anything is launched.
+ */
+#ifndef FD_H_
+#define FD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FD_VERSION 100
+
+enum {
+    FD_OK = 0,
+    FD_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, n_splits out of range ...   */
+    FD_ERR_UNSUPPORTED = -2, /* a shape the kernels are not built for (D != 128, G > 16 ...) */
+    FD_ERR_WORKSPACE = -3,   /* workspace allocation failed / too small for this call        */
+    FD_ERR_HIP = -4          /* a HIP runtime call failed (no device, launch error)          */
+};
+
+/* Keys per split used when the library picks the split count itself. */
+#define FD_ADAPTIVE_SPLIT_KEYS 512
+/* Upper bound accepted for fd_config.max_splits. */
+#define FD_MAX_SPLITS 1024
+
+typedef struct fd_handle_s* fd_handle_t;
+
+/*
+ * Problem shape, fixed per handle.
+ *   B           sequences in the batch (each contributes one query token)
+ *   Hq, Hkv     query heads and KV heads; Hq % Hkv == 0; query head h reads KV
+ *               head h / (Hq/Hkv) (consecutive query heads share a KV head)
+ *   D           head dimension; only 128 is built
+ *   S_max       row capacity of the KV cache per (sequence, KV head)
+ *   max_splits  largest split count any call on this handle may use
+ *               (1 .. FD_MAX_SPLITS); sizes the partial workspace
+ *   kv_layout   0 = contiguous [B, Hkv, S_max, D] (the only layout)
+ *   scale       softmax scale; 0 means 1/sqrt(D).  Applied in fp32 to the
+ *               fp32 dot product (never folded into a re-rounded bf16 q).
+ */
+typedef struct {
+    int32_t B, Hq, Hkv, D, S_max;
+    int32_t max_splits;
+    int32_t kv_layout;
+    float scale;
+} fd_config;
+
+/* Bytes of device workspace fd_create() allocates for cfg (0 if cfg is invalid). */
+size_t fd_workspace_bytes(const fd_config* cfg);
+
+/*
+ * Validates cfg, allocates the workspace on the current HIP device (partials
+ * [B,Hkv,max_splits,G,D] fp32, their LSEs, one arrival counter per tile) and
+ * zeroes the counters.  Synchronous.  *out receives the handle.
+ */
+int fd_create(const fd_config* cfg, fd_handle_t* out);
+
+/* Frees the workspace and the handle.  NULL is FD_ERR_INVALID_ARG. */
+int fd_destroy(fd_handle_t h);
+
+/*
+ * Re-zeroes the arrival counters on `stream` (a hipStream_t, NULL = default
+ * stream).  Only needed after a call was aborted mid-kernel: every completed
+ * call leaves the counters at zero by itself.
+ */
+int fd_reset(fd_handle_t h, void* stream);
+
+/*
+ * Fused Flash Decode (Algorithm 4 with Part 1 and Part 2 in one kernel).
+ *
+ *   q        [B, Hq, D]          bf16, device
+ *   k_cache  [B, Hkv, S_max, D]  bf16, device; 16-byte aligned
+ *   v_cache  [B, Hkv, S_max, D]  bf16, device; 16-byte aligned
+ *   seq_lens [B] int32, device; 0 <= seq_lens[b] <= S_max.  Read on the device:
+ *            the host never waits for it.  Rows >= seq_lens[b] are never read.
+ *   out      [B, Hq, D] fp32, device:  softmax(scale * q K^T) V
+ *   lse      [B, Hq]    fp32, device, natural log of sum_j exp(score_j);
+ *            may be NULL (then it is not written)
+ *   n_splits > 0: every sequence is cut into exactly n_splits contiguous key
+ *                 ranges (trailing ranges may be empty); n_splits <= max_splits.
+ *            = 0: adaptive, n_b = clamp(ceil(seq_lens[b]/512), 1, max_splits),
+ *                 computed on the device.
+ *   stream   hipStream_t (NULL = default stream)
+ *
+ * seq_lens[b] == 0 gives out = 0 and lse = -inf for that sequence.
+ * Accumulation is fp32; results match an fp64 evaluation of the definition to
+ * about 1e-5 relative on N(0,1) data.
+ */
+int fd_decode(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
+              const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream);
+
+/*
+ * Bulk-synchronous baseline (Section 4.2.2): same arguments, same results bit
+ * for bit; two launches (partials, then combine) on `stream`.
+ */
+int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
+                  const int32_t* seq_lens, float* out, float* lse, int32_t n_splits,
+                  void* stream);
+
+/*
+ * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.
+ *   FD_OPT_PATH          0 auto (MFMA kernel when Hq/Hkv >= 8, VALU kernel below),
+ *                        1 force VALU (Hq/Hkv <= 8 only), 2 force MFMA
+ *   FD_OPT_XCD_GROUPS    0 auto, 1 = one global item list, 8 = items of a tile
+ *                        stay on one XCD (tile t -> workgroups with id % 8 == t % 8)
+ *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto)
+ *   FD_INFO_*            read-only, through fd_get_option
+ */
+enum {
+    FD_OPT_PATH = 1,
+    FD_OPT_XCD_GROUPS = 2,
+    FD_OPT_WGS_PER_CU = 3,
+    FD_INFO_NUM_CUS = 100,
+    FD_INFO_LAST_GRID = 101,   /* workgroups of the last fused / split launch */
+    FD_INFO_LAST_PATH = 102    /* 1 VALU, 2 MFMA */
+};
+int fd_set_option(fd_handle_t h, int32_t key, int32_t value);
+int fd_get_option(fd_handle_t h, int32_t key, int32_t* value);
+
+/*
+ * Test aid: fills the partial workspace with NaN on `stream` (counters are left
+ * alone), so that a combine that reads a partial nobody wrote shows up.
+ */
+int fd_debug_poison_workspace(fd_handle_t h, void* stream);
+/* Test aid: copies the arrival counters to host memory (synchronous); n = B*Hkv. */
+int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n);
+
+/* Text of the calling thread's last error ("" if none). Never NULL. */
+const char* fd_last_error(void);
+int fd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FD_H_ */

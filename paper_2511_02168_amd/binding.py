@@ -1,0 +1,196 @@
+"""ctypes binding over libfd.so -- argument marshalling only.
+
+Function names and argument order follow include/fd.h.  Tensors are torch
+tensors on the GPU (torch supplies device memory and streams, nothing else);
+every step of the computation runs in the library's HIP kernels.  If libfd.so
+has not been built the import of the library fails loudly: there is no CPU or
+PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfd.so")
+
+FD_OK, FD_ERR_INVALID_ARG, FD_ERR_UNSUPPORTED, FD_ERR_WORKSPACE, FD_ERR_HIP = 0, -1, -2, -3, -4
+FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU = 1, 2, 3
+FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH = 100, 101, 102
+
+EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
+           "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
+           "fd_last_error", "fd_version"]
+
+
+class fd_config(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("S_max", ctypes.c_int32), ("max_splits", ctypes.c_int32),
+                ("kv_layout", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class FdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libfd error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it was never built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2511_02168_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.fd_workspace_bytes.restype = ctypes.c_size_t
+        L.fd_workspace_bytes.argtypes = [ctypes.POINTER(fd_config)]
+        L.fd_create.restype = ctypes.c_int
+        L.fd_create.argtypes = [ctypes.POINTER(fd_config), ctypes.POINTER(vp)]
+        L.fd_destroy.restype = ctypes.c_int
+        L.fd_destroy.argtypes = [vp]
+        L.fd_reset.restype = ctypes.c_int
+        L.fd_reset.argtypes = [vp, vp]
+        for fn in (L.fd_decode, L.fd_decode_bsp):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
+        L.fd_set_option.restype = ctypes.c_int
+        L.fd_set_option.argtypes = [vp, i32, i32]
+        L.fd_get_option.restype = ctypes.c_int
+        L.fd_get_option.argtypes = [vp, i32, ctypes.POINTER(i32)]
+        L.fd_debug_poison_workspace.restype = ctypes.c_int
+        L.fd_debug_poison_workspace.argtypes = [vp, vp]
+        L.fd_debug_read_counters.restype = ctypes.c_int
+        L.fd_debug_read_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), i32]
+        L.fd_last_error.restype = ctypes.c_char_p
+        L.fd_last_error.argtypes = []
+        L.fd_version.restype = ctypes.c_int
+        L.fd_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def fd_last_error() -> str:
+    return lib().fd_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != FD_OK:
+        raise FdError(rc, fd_last_error())
+
+
+def fd_version() -> int:
+    return int(lib().fd_version())
+
+
+def fd_workspace_bytes(cfg: fd_config) -> int:
+    return int(lib().fd_workspace_bytes(ctypes.byref(cfg)))
+
+
+def fd_create(cfg: fd_config) -> ctypes.c_void_p:
+    h = ctypes.c_void_p()
+    _check(lib().fd_create(ctypes.byref(cfg), ctypes.byref(h)))
+    return h
+
+
+def fd_destroy(h) -> None:
+    _check(lib().fd_destroy(h))
+
+
+def fd_reset(h, stream: int = 0) -> None:
+    _check(lib().fd_reset(h, ctypes.c_void_p(stream)))
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def fd_decode(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:
+    _check(lib().fd_decode(h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out), _ptr(lse),
+                           int(n_splits), ctypes.c_void_p(stream)))
+
+
+def fd_decode_bsp(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:
+    _check(lib().fd_decode_bsp(h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out), _ptr(lse),
+                               int(n_splits), ctypes.c_void_p(stream)))
+
+
+def fd_set_option(h, key: int, value: int) -> None:
+    _check(lib().fd_set_option(h, key, value))
+
+
+def fd_get_option(h, key: int) -> int:
+    v = ctypes.c_int32()
+    _check(lib().fd_get_option(h, key, ctypes.byref(v)))
+    return int(v.value)
+
+
+def fd_debug_poison_workspace(h, stream: int = 0) -> None:
+    _check(lib().fd_debug_poison_workspace(h, ctypes.c_void_p(stream)))
+
+
+def fd_debug_read_counters(h, n: int):
+    buf = (ctypes.c_uint32 * n)()
+    _check(lib().fd_debug_read_counters(h, buf, n))
+    return list(buf)
+
+
+class FlashDecode:
+    """Convenience owner of one handle: shapes fixed at construction."""
+
+    def __init__(self, B: int, Hq: int, Hkv: int, S_max: int, max_splits: int = 256, D: int = 128,
+                 scale: float = 0.0):
+        self.cfg = fd_config(B, Hq, Hkv, D, S_max, max_splits, 0, scale)
+        self.h = fd_create(self.cfg)
+
+    def close(self) -> None:
+        if self.h is not None:
+            fd_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def _check_tensors(self, q, k, v, seq_lens, out, lse):
+        import torch
+        c = self.cfg
+        assert q.is_cuda and k.is_cuda and v.is_cuda and seq_lens.is_cuda and out.is_cuda
+        assert q.dtype == torch.bfloat16 and k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
+        assert seq_lens.dtype == torch.int32 and out.dtype == torch.float32
+        assert tuple(q.shape) == (c.B, c.Hq, c.D) and q.is_contiguous()
+        assert tuple(k.shape) == (c.B, c.Hkv, c.S_max, c.D) and k.is_contiguous()
+        assert tuple(v.shape) == (c.B, c.Hkv, c.S_max, c.D) and v.is_contiguous()
+        assert tuple(seq_lens.shape) == (c.B,) and seq_lens.is_contiguous()
+        assert tuple(out.shape) == (c.B, c.Hq, c.D) and out.is_contiguous()
+        if lse is not None:
+            assert lse.is_cuda and lse.dtype == torch.float32 and tuple(lse.shape) == (c.B, c.Hq) and lse.is_contiguous()
+
+    def decode(self, q, k, v, seq_lens, n_splits: int, out=None, lse=None, bsp: bool = False,
+               stream: Optional[int] = None, want_lse: bool = True):
+        import torch
+        c = self.cfg
+        if out is None:
+            out = torch.empty(c.B, c.Hq, c.D, device=q.device, dtype=torch.float32)
+        if lse is None and want_lse:
+            lse = torch.empty(c.B, c.Hq, device=q.device, dtype=torch.float32)
+        self._check_tensors(q, k, v, seq_lens, out, lse)
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        fn = fd_decode_bsp if bsp else fd_decode
+        fn(self.h, q, k, v, seq_lens, out, lse, n_splits, stream)
+        return out, lse

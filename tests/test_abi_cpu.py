@@ -1,0 +1,89 @@
+"""CPU-only checks of the C ABI: the built library loads, exports every symbol
+include/fd.h declares, and rejects bad arguments on the host before any device
+work (no compute calls are made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_02168_amd import binding as fd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_is_built_and_loads():
+    assert os.path.exists(fd.LIB_PATH), "run `python -m paper_2511_02168_amd.build` first"
+    assert fd.fd_version() == 100
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert "fd_decode" in names and "fd_decode_bsp" in names and len(names) >= 12
+    raw = ctypes.CDLL(fd.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), f"{n} declared in fd.h but not exported"
+    assert sorted(fd.EXPORTS) == names, "binding's export list and fd.h disagree"
+
+
+def good_cfg(**kw):
+    base = dict(B=2, Hq=8, Hkv=2, D=128, S_max=4096, max_splits=16, kv_layout=0, scale=0.0)
+    base.update(kw)
+    return fd.fd_config(*[base[k] for k in ("B", "Hq", "Hkv", "D", "S_max", "max_splits", "kv_layout", "scale")])
+
+
+def test_workspace_bytes_formula():
+    cfg = good_cfg()
+    tiles, G, n = 4, 4, 16
+    expect = tiles * n * G * 128 * 4 + tiles * n * G * 4 + 256      # partials, their LSEs, counters (256-byte rounded)
+    assert fd.fd_workspace_bytes(cfg) == expect
+    assert fd.fd_workspace_bytes(good_cfg(D=64)) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), fd.FD_ERR_INVALID_ARG),
+    (dict(Hq=7), fd.FD_ERR_INVALID_ARG),
+    (dict(S_max=-5), fd.FD_ERR_INVALID_ARG),
+    (dict(max_splits=0), fd.FD_ERR_INVALID_ARG),
+    (dict(max_splits=100000), fd.FD_ERR_INVALID_ARG),
+    (dict(scale=-1.0), fd.FD_ERR_INVALID_ARG),
+    (dict(scale=float("nan")), fd.FD_ERR_INVALID_ARG),
+    (dict(D=64), fd.FD_ERR_UNSUPPORTED),
+    (dict(kv_layout=1), fd.FD_ERR_UNSUPPORTED),
+    (dict(Hq=64, Hkv=2), fd.FD_ERR_UNSUPPORTED),
+])
+def test_create_rejects_bad_config_before_touching_the_device(kw, code):
+    with pytest.raises(fd.FdError) as e:
+        fd.fd_create(good_cfg(**kw))
+    assert e.value.code == code
+    assert fd.fd_last_error() != ""
+
+
+def test_null_handles_and_pointers():
+    L = fd.lib()
+    assert L.fd_destroy(None) == fd.FD_ERR_INVALID_ARG
+    assert L.fd_reset(None, None) == fd.FD_ERR_INVALID_ARG
+    assert L.fd_decode(None, None, None, None, None, None, None, 1, None) == fd.FD_ERR_INVALID_ARG
+    assert L.fd_decode_bsp(None, None, None, None, None, None, None, 1, None) == fd.FD_ERR_INVALID_ARG
+    assert L.fd_set_option(None, 1, 0) == fd.FD_ERR_INVALID_ARG
+    assert L.fd_create(None, None) == fd.FD_ERR_INVALID_ARG
+    assert "handle" in fd.fd_last_error() or "NULL" in fd.fd_last_error()
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2511_02168_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "fd_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2511_02168_amd" not in text and "libfd.so" not in text, f

@@ -1,0 +1,288 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle.
+
+Tolerances are the benchmark definition's: out within atol = rtol = 2e-3,
+LSE within 1e-4 relative (|d| <= 1e-4 * max(1, |ref|)).  Fused and
+bulk-synchronous results must be bitwise equal (same partials, fixed-order
+merge).  Inputs are seeded synthetic tensors (paper_2511_02168_amd.inputs).
+"""
+import dataclasses
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_02168_amd import binding as fd
+from paper_2511_02168_amd import inputs as fi
+
+pytestmark = pytest.mark.gpu
+
+ATOL = RTOL = 2e-3
+LSE_RTOL = 1e-4
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def check_out(got, ref, what):
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - ref)
+    bound = ATOL + RTOL * np.abs(ref)
+    worst = float((err / bound).max()) if err.size else 0.0
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    assert worst <= 1.0, f"{what}: out error {err.max():.3e} exceeds tolerance (ratio {worst:.2f})"
+    return float(err.max())
+
+
+def check_lse(got, ref, what):
+    got = np.asarray(got, dtype=np.float64)
+    inf = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(got), inf), f"{what}: -inf pattern of lse differs"
+    err = np.abs(got[~inf] - ref[~inf])
+    bound = LSE_RTOL * np.maximum(1.0, np.abs(ref[~inf]))
+    assert (err <= bound).all(), f"{what}: lse error {err.max():.3e} exceeds 1e-4 relative"
+    return float(err.max()) if err.size else 0.0
+
+
+def run_both(dec, inp, n_splits, want_lse=True):
+    """Fused and BSP through the C ABI; asserts bitwise equality; returns numpy results."""
+    out_f, lse_f = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n_splits, want_lse=want_lse)
+    out_b, lse_b = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n_splits, bsp=True, want_lse=want_lse)
+    torch.cuda.synchronize()
+    assert torch.equal(out_f.view(torch.int32), out_b.view(torch.int32)), "fused and BSP outputs differ bitwise"
+    if want_lse:
+        assert torch.equal(lse_f.view(torch.int32), lse_b.view(torch.int32)), "fused and BSP lse differ bitwise"
+    n_tiles = dec.cfg.B * dec.cfg.Hkv
+    assert all(c == 0 for c in fd.fd_debug_read_counters(dec.h, n_tiles)), "arrival counters not re-armed"
+    return out_f.cpu().numpy(), (lse_f.cpu().numpy() if want_lse else None)
+
+
+def full_parity(wl, inp, n_splits, max_splits=None, what=""):
+    ms = max_splits or max(n_splits, 1)
+    with fd.FlashDecode(inp.q.shape[0], wl.Hq, wl.Hkv, inp.k.shape[2], max_splits=ms) as dec:
+        fd.fd_debug_poison_workspace(dec.h)
+        out, lse = run_both(dec, inp, n_splits)
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    eo = check_out(out, ref_o, what)
+    el = check_lse(lse, ref_l, what)
+    say(f"  {what}: max |out err| {eo:.2e}, max |lse err| {el:.2e}")
+
+
+# ---------------------------------------------------------------- the five workloads
+
+def test_c1_tiny_mha_full():
+    wl = fi.workload("c1")
+    say(f"case {wl.name} B{wl.B} Hq{wl.Hq} Hkv{wl.Hkv} S{wl.S_max} n{wl.n_splits}")
+    inp = fi.make_inputs(wl, "cuda")
+    full_parity(wl, inp, wl.n_splits, what=wl.name)
+
+
+def test_c2_gqa_full():
+    wl = fi.workload("c2")
+    say(f"case {wl.name} B{wl.B} Hq{wl.Hq} Hkv{wl.Hkv} S{wl.S_max} n{wl.n_splits}")
+    inp = fi.make_inputs(wl, "cuda")
+    full_parity(wl, inp, wl.n_splits, what=wl.name)
+
+
+def test_c3_group8_full():
+    wl = fi.workload("c3")
+    say(f"case {wl.name} B{wl.B} Hq{wl.Hq} Hkv{wl.Hkv} S{wl.S_max} n{wl.n_splits}")
+    inp = fi.make_inputs(wl, "cuda")
+    full_parity(wl, inp, wl.n_splits, what=wl.name)
+
+
+def _sampled_rows_check(wl, inp, out, lse, rows, what):
+    """Oracle on single (b, h) rows, each computed one by one from its own K/V slice."""
+    G = wl.G
+    worst_o = worst_l = 0.0
+    for (b, h) in rows:
+        S = int(inp.seq_lens[b])
+        kvh = h // G
+        qb = fi.bits(inp.q[b:b + 1, h:h + 1])
+        kb = fi.bits(inp.k[b:b + 1, kvh:kvh + 1, :max(S, 1)])
+        vb = fi.bits(inp.v[b:b + 1, kvh:kvh + 1, :max(S, 1)])
+        ro, rl = oracle.decode(qb, kb, vb, np.array([S], np.int32))
+        worst_o = max(worst_o, check_out(out[b, h], ro[0, 0], f"{what} row ({b},{h}) S={S}"))
+        worst_l = max(worst_l, check_lse(lse[b, h:h + 1], rl[0], f"{what} row ({b},{h}) S={S}"))
+    say(f"  {what}: {len(rows)} sampled rows, max |out err| {worst_o:.2e}, max |lse err| {worst_l:.2e}")
+
+
+def test_c4_ragged_full_size_sampled():
+    wl = fi.workload("c4")
+    say(f"case {wl.name} B{wl.B} Hq{wl.Hq} Hkv{wl.Hkv} S<= {wl.S_max} adaptive splits, full size, sampled rows")
+    inp = fi.make_inputs(wl, "cuda")
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=64) as dec:
+        fd.fd_debug_poison_workspace(dec.h)
+        out, lse = run_both(dec, inp, 0)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()      # NaN padding past seq_lens was never read
+    sl = inp.seq_lens.cpu().numpy()
+    rng = np.random.default_rng(wl.seed)
+    bs = {int(np.argmin(sl)), int(np.argmax(sl))} | set(int(x) for x in rng.choice(wl.B, 6, replace=False))
+    rows = [(b, int(rng.integers(0, wl.Hq))) for b in sorted(bs)] + [(int(np.argmax(sl)), 0), (int(np.argmin(sl)), wl.Hq - 1)]
+    _sampled_rows_check(wl, inp, out, lse, rows, wl.name)
+
+
+def test_c4_ragged_reduced_full_oracle():
+    wl = fi.workload("c4")
+    say(f"case {wl.name} reduced to B=16, S_max=3000 (ragged, NaN padded), adaptive and fixed splits, full oracle")
+    inp = fi.make_inputs(wl, "cuda", S_max=3000, B=16)
+    full_parity(wl, inp, 0, max_splits=16, what=wl.name + "/reduced/adaptive")
+    full_parity(wl, inp, 5, max_splits=16, what=wl.name + "/reduced/n5")
+
+
+def test_c5_long_context_full_size_sampled():
+    wl = fi.workload("c5")
+    say(f"case {wl.name} B{wl.B} Hq{wl.Hq} Hkv{wl.Hkv} S{wl.S_max} n{wl.n_splits}, full size, sampled rows")
+    inp = fi.make_inputs(wl, "cuda")
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=wl.n_splits) as dec:
+        fd.fd_debug_poison_workspace(dec.h)
+        out, lse = run_both(dec, inp, wl.n_splits)
+    rows = [(0, h) for h in (0, 7, 13, 26, 35, 41, 54, 63)]
+    _sampled_rows_check(wl, inp, out, lse, rows, wl.name)
+    # peaked attention: the aligned keys must dominate (lse well above the ln(S) of flat attention)
+    assert float(lse.min()) > np.log(wl.S_max) + 1.0
+
+
+def test_c5_reduced_full_oracle():
+    wl = fi.workload("c5")
+    say(f"case {wl.name} reduced to S=8200, n_splits 16 and 7, full oracle")
+    inp = fi.make_inputs(wl, "cuda", S_max=8200)
+    full_parity(wl, inp, 16, what=wl.name + "/reduced/n16")
+    full_parity(wl, inp, 7, what=wl.name + "/reduced/n7")
+
+
+# ---------------------------------------------------------------- edge shapes
+
+def _generic(B, Hq, Hkv, S_max, seed, ragged=False, k_scale=1.0):
+    return fi.Workload(f"edge_b{B}_hq{Hq}_hkv{Hkv}_s{S_max}", seed, B=B, Hq=Hq, Hkv=Hkv, S_max=S_max, n_splits=0,
+                       ragged=ragged, k_scale=k_scale)
+
+
+@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 63, 64, 65, 127, 129, 511, 512, 513, 1000])
+def test_edge_sequence_lengths(S):
+    wl = _generic(2, 8, 2, S, 100 + S)
+    say(f"case edge S={S} G=4, n_splits 1, 3, adaptive")
+    inp = fi.make_inputs(wl, "cuda")
+    for n in (1, 3, 0):
+        full_parity(wl, inp, n, max_splits=8, what=f"S={S} n={n}")
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_group_size(G):
+    wl = _generic(3, 2 * G, 2, 777, 200 + G, ragged=True)
+    say(f"case group size G={G}, ragged S<=777, n_splits 4 and adaptive")
+    inp = fi.make_inputs(wl, "cuda")
+    full_parity(wl, inp, 4, max_splits=8, what=f"G={G} n=4")
+    full_parity(wl, inp, 0, max_splits=8, what=f"G={G} adaptive")
+
+
+def test_more_splits_than_key_blocks():
+    wl = _generic(2, 4, 1, 100, 300)
+    say("case n_splits=16 over 100 keys (most splits empty)")
+    inp = fi.make_inputs(wl, "cuda")
+    full_parity(wl, inp, 16, what="n16/S100")
+
+
+def test_zero_and_one_length_sequences_in_a_batch():
+    wl = _generic(5, 8, 2, 600, 400)
+    say("case seq_lens = [0, 1, 600, 64, 0]")
+    inp = fi.make_inputs(wl, "cuda")
+    inp.seq_lens = torch.tensor([0, 1, 600, 64, 0], dtype=torch.int32, device="cuda")
+    for b, s in enumerate([0, 1, 600, 64, 0]):            # poison everything past the end
+        inp.k[b, :, s:] = float("nan")
+        inp.v[b, :, s:] = float("nan")
+    for n in (0, 1, 4):
+        full_parity(wl, inp, n, max_splits=4, what=f"zero/one lengths n={n}")
+
+
+def test_lse_pointer_may_be_null():
+    wl = _generic(2, 8, 2, 700, 500)
+    say("case lse = NULL")
+    inp = fi.make_inputs(wl, "cuda")
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=4) as dec:
+        out, _ = run_both(dec, inp, 4, want_lse=False)
+    ref_o, _ = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    check_out(out, ref_o, "lse=NULL")
+
+
+def test_peaked_two_key_attention():
+    """Two dominant keys with opposite values: the hardest case for weight rounding."""
+    wl = _generic(1, 8, 1, 256, 600)
+    say("case two dominant keys, opposite values (G=8)")
+    inp = fi.make_inputs(wl, "cuda")
+    q32 = inp.q.float()
+    for h in range(8):                      # keys 2h and 2h+1 aligned with head h, others left random
+        qh = q32[0, h]
+        inp.k[0, 0, 2 * h] = (qh * 1.5).to(torch.bfloat16)
+        inp.k[0, 0, 2 * h + 1] = (qh * 1.5).to(torch.bfloat16)
+        inp.v[0, 0, 2 * h] = 1.0
+        inp.v[0, 0, 2 * h + 1] = -1.0
+    full_parity(wl, inp, 2, what="two-key peaked")
+
+
+def test_custom_scale():
+    wl = _generic(2, 4, 2, 300, 700)
+    say("case scale = 0.25 (not 1/sqrt(D))")
+    inp = fi.make_inputs(wl, "cuda")
+    cfg = dict(B=wl.B, Hq=wl.Hq, Hkv=wl.Hkv, S_max=wl.S_max, max_splits=4, scale=0.25)
+    with fd.FlashDecode(**cfg) as dec:
+        out, lse = run_both(dec, inp, 3)
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy(), scale=0.25)
+    check_out(out, ref_o, "scale 0.25")
+    check_lse(lse, ref_l, "scale 0.25")
+
+
+# ---------------------------------------------------------------- protocol checks
+
+def test_repeat_determinism_with_poisoned_workspace():
+    wl = fi.workload("c2")
+    say("case 200 repeated fused calls on c2 (S reduced to 2048), NaN-poisoned workspace before each")
+    inp = fi.make_inputs(wl, "cuda", S_max=2048)
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, 2048, max_splits=16) as dec:
+        first_o, first_l = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+        first_o, first_l = first_o.clone(), first_l.clone()
+        for it in range(200):
+            fd.fd_debug_poison_workspace(dec.h, torch.cuda.current_stream().cuda_stream)
+            o, l = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+            assert torch.equal(o.view(torch.int32), first_o.view(torch.int32)), f"iteration {it}: output changed"
+            assert torch.equal(l.view(torch.int32), first_l.view(torch.int32)), f"iteration {it}: lse changed"
+        assert all(c == 0 for c in fd.fd_debug_read_counters(dec.h, wl.B * wl.Hkv))
+
+
+def test_xcd_grouping_and_grid_size_do_not_change_results():
+    wl = fi.workload("c2")
+    say("case c2 (S reduced to 4096): XCD groups 1 vs 8, 1..4 workgroups per CU -> bitwise equal")
+    inp = fi.make_inputs(wl, "cuda", S_max=4096)
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, 4096, max_splits=16) as dec:
+        base, base_l = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+        base, base_l = base.clone(), base_l.clone()
+        for xg in (1, 8):
+            for per_cu in (1, 2, 4):
+                fd.fd_set_option(dec.h, fd.FD_OPT_XCD_GROUPS, xg)
+                fd.fd_set_option(dec.h, fd.FD_OPT_WGS_PER_CU, per_cu)
+                for bsp in (False, True):
+                    o, l = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16, bsp=bsp)
+                    assert torch.equal(o.view(torch.int32), base.view(torch.int32)), (xg, per_cu, bsp)
+                    assert torch.equal(l.view(torch.int32), base_l.view(torch.int32)), (xg, per_cu, bsp)
+
+
+def test_argument_errors_on_device():
+    say("case argument validation with a live handle")
+    with fd.FlashDecode(1, 8, 8, 1024, max_splits=4) as dec:
+        t = torch.zeros(1, 8, 128, device="cuda", dtype=torch.bfloat16)
+        kv = torch.zeros(1, 8, 1024, 128, device="cuda", dtype=torch.bfloat16)
+        sl = torch.full((1,), 1024, device="cuda", dtype=torch.int32)
+        out = torch.empty(1, 8, 128, device="cuda")
+        with pytest.raises(fd.FdError) as e:
+            fd.fd_decode(dec.h, t, kv, kv, sl, out, None, 5)        # n_splits > max_splits
+        assert e.value.code == fd.FD_ERR_INVALID_ARG
+        with pytest.raises(fd.FdError) as e:
+            fd.fd_decode(dec.h, None, kv, kv, sl, out, None, 4)
+        assert e.value.code == fd.FD_ERR_INVALID_ARG
+        with pytest.raises(fd.FdError) as e:
+            fd.fd_decode(dec.h, t, kv, kv, sl, out, None, -1)
+        assert e.value.code == fd.FD_ERR_INVALID_ARG
+        assert fd.fd_get_option(dec.h, fd.FD_INFO_NUM_CUS) == 256
