@@ -70,9 +70,13 @@ __device__ __forceinline__ int split_keys_of(int S, int n)
 // Workgroup w belongs to XCD group x = w % X (the hardware deals workgroups to
 // the 8 XCDs round-robin, so with X = 8 a group is one XCD and its L2).  Group x
 // owns tiles t = x, x+X, x+2X, ...; its items are those tiles' splits in order.
-// Member wl = w / X of the group takes items wl, wl + members, ...
+// Member wl = w / X of the group takes the contiguous block of items
+// [wl*E/members, (wl+1)*E/members): consecutive splits of one tile become ONE
+// longer key range (one partial, one arrival), and a workgroup streams long
+// contiguous stretches of the cache.
 struct WorkList {
     int x, wl, members, n_tiles, n_items;
+    int first, last;      // this workgroup's block of items [first, last)
 };
 
 struct Item {
@@ -90,6 +94,8 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     wlst.n_tiles = wlst.x < T ? (T - wlst.x + X - 1) / X : 0;
     if (p.n_splits > 0) {
         wlst.n_items = wlst.n_tiles * p.n_splits;
+        wlst.first = (int)((long long)wlst.wl * wlst.n_items / wlst.members);
+        wlst.last = (int)((long long)(wlst.wl + 1) * wlst.n_items / wlst.members);
         return;
     }
     // adaptive: block-wide exclusive scan of n_b over the group's tiles
@@ -118,6 +124,8 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     if (tid == kWgThreads - 1) pre[wlst.n_tiles] = scan_tmp[tid];
     __syncthreads();
     wlst.n_items = pre[wlst.n_tiles];
+    wlst.first = (int)((long long)wlst.wl * wlst.n_items / wlst.members);
+    wlst.last = (int)((long long)(wlst.wl + 1) * wlst.n_items / wlst.members);
 }
 
 __device__ __forceinline__ Item worklist_item(const Params& p, const WorkList& wlst, const int* pre, int e)
@@ -157,8 +165,44 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
 
+// 128-bit load of K/V data that is used once: the non-temporal hint keeps the
+// stream from displacing useful lines and measurably raises read bandwidth.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p)
+{
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// ---- exchange of partials between workgroups ----------------------------------
+// A gfx950 device has 8 XCDs, each with its own L2 that is not kept coherent
+// with the others.  An agent-scope release/acquire FENCE is implemented as a
+// write-back / invalidate of a whole L2, far too heavy to run once per item.
+// Partials and counters are therefore written and read only with agent-scope
+// relaxed atomic accesses (sc1 stores write through to the device-coherent
+// level, sc1 loads do not use a possibly stale L1/L2 line), and the order
+// "partials, then counter" is kept by waiting for the stores' acknowledgements
+// (s_waitcnt vmcnt(0)) before the workgroup barrier that precedes the counter
+// increment.  No other data travels between workgroups inside a launch.
+__device__ __forceinline__ void store_agent(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// two adjacent floats (8-byte aligned) in one coherent access
+__device__ __forceinline__ float2 load_agent2(const float* p)
+{
+    const unsigned long long w =
+        __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__builtin_bit_cast(float, (uint32_t)w), __builtin_bit_cast(float, (uint32_t)(w >> 32)));
+}
+__device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x)
@@ -190,55 +234,142 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
-// ---- Combine (Algorithm 4, Part 2), one workgroup per tile -------------------
-// Merges the n partials of tile (b, kvh) into out / lse, in split order
-// i = 0..n-1 (fixed order: results do not depend on which workgroup runs this).
-// Partials with lse = -inf (empty key range) have weight 0 and their o rows,
-// which nobody wrote, are ignored.
-// sm: 2*G floats of LDS.  Ends with every thread past its last read of sm.
-template <int G>
-__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, float* sm)
+// ---- end of an item: merge the workgroup's 4 wave states, normalise, store ------
+// Each wave leaves its running max m, sum l and unnormalised accumulator for the
+// ROWS query heads of the tile here; all in base-2 units.
+template <int ROWS>
+struct ItemSmem {
+    float m[kWaves][ROWS];
+    float l[kWaves][ROWS];
+    float acc[kWaves][ROWS][kD];
+};
+
+// a6: o = sum_w acc_w 2^(m_w - M) / sum_w l_w 2^(m_w - M), lse = M + log2(sum).
+// SHARED: the destination is a partial another workgroup may read in this launch
+// (coherent stores).  Call with the wave states written and a barrier passed;
+// returns with every thread past its last read of sm.
+template <int ROWS, bool SHARED>
+__device__ inline void item_finish(const ItemSmem<ROWS>& sm, int G, float* dst_o, float* dst_lse, float lse_mul)
 {
+    for (int idx = threadIdx.x; idx < G * kD; idx += kWgThreads) {
+        const int g = idx / kD, d = idx % kD;
+        float M = sm.m[0][g];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm.m[w][g]);
+        float L = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float f = fast_exp2(sm.m[w][g] - M);
+            L += sm.l[w][g] * f;
+            o += sm.acc[w][g][d] * f;
+        }
+        const float res = o / L, res_lse = (M + fast_log2(L)) * lse_mul;
+        if (SHARED) {
+            store_agent(&dst_o[idx], res);
+            if (d == 0) store_agent(&dst_lse[g], res_lse);
+        } else {
+            dst_o[idx] = res;
+            if (d == 0 && dst_lse) dst_lse[g] = res_lse;
+        }
+    }
+    __syncthreads();
+}
+
+// ---- Combine (Algorithm 4, Part 2), one workgroup per tile -------------------
+// Merges the partials of tile (b, kvh) into out / lse.  Of the tile's n slots only
+// the "live" ones hold a partial: a workgroup that attended several consecutive
+// splits in one go wrote a single partial into the first slot and lse = -inf
+// into the others (as it does for splits with no keys).  Rows are merged in
+// ascending slot order within fixed row slices, so the result does not depend
+// on which workgroup runs this.
+constexpr int kMaxSplits = 1024;
+
+struct CombineSmem {
+    int live[kMaxSplits];       // live slots, ascending
+    int n_live;
+    float M[16], invL[16];
+    float4 red[kWgThreads];     // cross-slice reduction
+};
+
+__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm)
+{
+    const int G = p.G;          // <= 16
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const float* plse = p.part_lse + (size_t)tile * p.max_splits * G;
-    const float4* po = reinterpret_cast<const float4*>(p.part_o + (size_t)tile * p.max_splits * G * kD);
+    const float* po = p.part_o + (size_t)tile * p.max_splits * G * kD;
 
+    // phase 0: wave 0 lists the live slots in ascending order
+    if (wave == 0) {
+        int count = 0;
+        for (int base = 0; base < n; base += 64) {
+            const int i = base + lane;
+            const bool live = i < n && load_agent(&plse[i * G]) != -INFINITY;
+            const unsigned long long mask = __ballot(live);
+            if (live) sm.live[count + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+            count += __popcll(mask);
+        }
+        if (lane == 0) sm.n_live = count;
+    }
+    __syncthreads();
+    const int n_live = sm.n_live;
+
+    // phase 1: per head, max and sum of the live rows' weights
     for (int g = wave; g < G; g += kWaves) {
         float mx = -INFINITY;
-        for (int i = lane; i < n; i += 64) mx = fmaxf(mx, plse[i * G + g]);
+        for (int k = lane; k < n_live; k += 64) mx = fmaxf(mx, load_agent(&plse[sm.live[k] * G + g]));
         mx = wave_max(mx);
         float sum = 0.f;
-        for (int i = lane; i < n; i += 64) {
-            const float v = plse[i * G + g];
-            sum += (v == -INFINITY) ? 0.f : fast_exp2(v - mx);
-        }
+        for (int k = lane; k < n_live; k += 64) sum += fast_exp2(load_agent(&plse[sm.live[k] * G + g]) - mx);
         sum = wave_sum(sum);
         if (lane == 0) {
-            sm[g] = mx;
-            sm[G + g] = sum > 0.f ? 1.0f / sum : 0.f;
-            if (p.lse) p.lse[(size_t)b * p.Hq + kvh * G + g] = sum > 0.f ? (mx + fast_log2(sum)) * kLn2 : -INFINITY;
+            sm.M[g] = mx;
+            sm.invL[g] = n_live > 0 ? 1.0f / sum : 0.f;
+            if (p.lse) p.lse[(size_t)b * p.Hq + kvh * G + g] = n_live > 0 ? (mx + fast_log2(sum)) * kLn2 : -INFINITY;
         }
     }
     __syncthreads();
 
+    // phase 2: out[g][d] = sum_k w_k[g] * o_k[g][d].  A thread owns one (g, 4 dims)
+    // pair; when there are fewer pairs than threads, R threads share a pair, each
+    // taking every R-th live row, and their sums are added in slice order.
+    const int kPairs = G * (kD / 4);
+    const int R = kPairs >= kWgThreads ? 1 : kWgThreads / kPairs;
     float4* dst = reinterpret_cast<float4*>(p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD);
-    for (int vi = tid; vi < G * (kD / 4); vi += kWgThreads) {
-        const int g = vi / (kD / 4), d4 = vi % (kD / 4);
-        const float M = sm[g], invL = sm[G + g];
+    for (int pbase = 0; pbase < kPairs; pbase += kWgThreads) {
+        const int pair = pbase + (R > 1 ? tid % kPairs : tid);
+        const int slice = R > 1 ? tid / kPairs : 0;
+        const bool active = pair < kPairs && slice < R;
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (active) {
+            const int g = pair / (kD / 4), d4 = pair % (kD / 4);
+            const float M = sm.M[g], invL = sm.invL[g];
 #pragma unroll 8
-        for (int i = 0; i < n; ++i) {
-            const float lw = plse[i * G + g];
-            const bool live = lw != -INFINITY;
-            const float w = live ? fast_exp2(lw - M) * invL : 0.f;
-            float4 x = po[(size_t)(i * G + g) * (kD / 4) + d4];
-            o.x += live ? w * x.x : 0.f;
-            o.y += live ? w * x.y : 0.f;
-            o.z += live ? w * x.z : 0.f;
-            o.w += live ? w * x.w : 0.f;
+            for (int k = slice; k < n_live; k += R) {
+                const int i = sm.live[k];
+                const float w = fast_exp2(load_agent(&plse[i * G + g]) - M) * invL;
+                const float* src = po + ((size_t)(i * G + g) * (kD / 4) + d4) * 4;
+                const float2 x01 = load_agent2(src), x23 = load_agent2(src + 2);
+                o.x += w * x01.x;
+                o.y += w * x01.y;
+                o.z += w * x23.x;
+                o.w += w * x23.y;
+            }
         }
-        dst[vi] = o;
+        if (R > 1) {
+            sm.red[tid] = o;
+            __syncthreads();
+            if (active && slice == 0) {
+                for (int r = 1; r < R; ++r) {
+                    const float4 t = sm.red[r * kPairs + pair];
+                    o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+                }
+                dst[pair] = o;
+            }
+            __syncthreads();
+        } else if (active) {
+            dst[pair] = o;
+        }
     }
     __syncthreads();
 }

@@ -13,6 +13,7 @@
 
 #include "fd_device.hpp"
 #include "fd_valu.hpp"
+#include "fd_mfma.hpp"
 
 namespace fd {
 
@@ -20,83 +21,153 @@ namespace fd {
 // Kernels
 // ---------------------------------------------------------------------------
 
+// How a workgroup attends one key range: on the vector ALUs ...
 template <int G>
-union __attribute__((aligned(16))) WgSmem {
-    ValuSmem<G> valu;
-    float comb[2 * G];
+struct ValuPath {
+    ItemSmem<G>* sm;
+    template <bool SHARED>
+    __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
+                                         float mul) const
+    {
+        valu_item<G, SHARED>(p, b, kvh, j0, j1, o, l, mul, *sm);
+    }
 };
 
-// Persistent split-KV kernel.  FUSED: steps a1-a8 in one launch (the workgroup
-// that completes a tile's last split merges the tile, paper Section 4.2.5 /
-// Algorithm 4 without barrier or second launch).  !FUSED: steps a1-a6 only
-// (kernel 1 of the bulk-synchronous baseline, Section 4.2.2).
-template <int G, bool FUSED>
-__global__ __launch_bounds__(kWgThreads, (G <= 5 ? 2 : 1)) void fd_valu_kernel(Params p)
+// ... or on the matrix cores, through an LDS ring of NST stages per wave.
+template <int NST>
+struct MfmaPath {
+    char* ring;
+    template <bool SHARED>
+    __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
+                                         float mul) const
+    {
+        mfma_item<NST, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+    }
+};
+
+struct SchedSmem {
+    int pre[kMaxGroupTiles + 1];
+    int scan_tmp[kWgThreads];
+    int is_last;
+};
+
+// The persistent loop of a workgroup.  FUSED: steps a1-a8 in one launch (the
+// workgroup that completes a tile's split count merges the tile: paper Section
+// 4.2.5 / Algorithm 4 without the barrier and without the second launch).
+// !FUSED: steps a1-a6 only (kernel 1 of the bulk-synchronous baseline, Section 4.2.2).
+template <bool FUSED, class Path>
+__device__ __forceinline__ void persistent_loop(const Params& p, const Path& path, SchedSmem& ss, CombineSmem& comb)
 {
-    __shared__ WgSmem<G> sm;
-    __shared__ int pre[kMaxGroupTiles + 1];
-    __shared__ int scan_tmp[kWgThreads];
-    __shared__ int is_last;
-
+    const int G = p.G;
     WorkList wl;
-    worklist_init(p, wl, pre, scan_tmp);
+    worklist_init(p, wl, ss.pre, ss.scan_tmp);
 
-    for (int e = wl.wl; e < wl.n_items; e += wl.members) {
-        const Item it = worklist_item(p, wl, pre, e);
+    int e = wl.first;
+    while (e < wl.last) {
+        // a run = the splits [split, s1) of one tile that fall into this workgroup's block
+        Item it = worklist_item(p, wl, ss.pre, e);
+        it.tile = __builtin_amdgcn_readfirstlane(it.tile);      // all of these are workgroup-uniform
+        it.b = __builtin_amdgcn_readfirstlane(it.b);
+        it.kvh = __builtin_amdgcn_readfirstlane(it.kvh);
+        it.split = __builtin_amdgcn_readfirstlane(it.split);
+        it.n = __builtin_amdgcn_readfirstlane(it.n);
+        it.S = __builtin_amdgcn_readfirstlane(it.S);
+        const int s1 = min(it.n, it.split + (wl.last - e));
+        const int run = s1 - it.split;
+        e += run;
         const int c = split_keys_of(it.S, it.n);
-        const int j0 = it.split * c;
-        const int j1 = min(j0 + c, it.S);
+        const int j0 = min(it.split * c, it.S);
+        const int j1 = min(s1 * c, it.S);
         const size_t slot = (size_t)it.tile * p.max_splits + it.split;
-        const bool direct = it.n == 1;       // a single split is already the final result
+        const bool direct = run == it.n;     // the whole tile in one go: this is the final result
 
-        if (j0 < j1) {
-            if (direct) {
-                float* o = p.out + ((size_t)it.b * p.Hq + (size_t)it.kvh * G) * kD;
-                float* l = p.lse ? p.lse + (size_t)it.b * p.Hq + it.kvh * G : nullptr;
-                valu_item<G>(p, it.b, it.kvh, j0, j1, o, l, kLn2, sm.valu);
-            } else {
-                valu_item<G>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f,
-                             sm.valu);
-            }
-        } else if (direct) {                 // empty sequence: out = 0, lse = -inf
+        if (direct) {
             float* o = p.out + ((size_t)it.b * p.Hq + (size_t)it.kvh * G) * kD;
-            for (int i = threadIdx.x; i < G * kD; i += kWgThreads) o[i] = 0.f;
-            if (p.lse && threadIdx.x < G) p.lse[(size_t)it.b * p.Hq + it.kvh * G + threadIdx.x] = -INFINITY;
-        } else {                             // empty split: weight zero in the combine
-            if (threadIdx.x < G) p.part_lse[slot * G + threadIdx.x] = -INFINITY;
+            float* l = p.lse ? p.lse + (size_t)it.b * p.Hq + it.kvh * G : nullptr;
+            if (j0 < j1) {
+                path.template item<false>(p, it.b, it.kvh, j0, j1, o, l, kLn2);
+            } else {                         // empty sequence: out = 0, lse = -inf
+                for (int i = threadIdx.x; i < G * kD; i += kWgThreads) o[i] = 0.f;
+                if (l && threadIdx.x < G) l[threadIdx.x] = -INFINITY;
+            }
+            // bulk-synchronous mode: tell kernel 2 that this tile needs no combine
+            if (!FUSED && threadIdx.x == 0) p.counters[it.tile] = 1u;
+            continue;
         }
 
-        if (FUSED && !direct) {
-            // a7: publish the partial, then count the arrival (Algorithm 4: push, then
-            // atomic increment of the flag).  a8: the last arriver of the tile combines.
-            __threadfence();
+        // a6: one partial for the run in its first slot; the run's other slots (and
+        // the first one too if the run has no keys) are marked empty
+        if (j0 < j1)
+            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f);
+        {
+            const int skip = j0 < j1 ? G : 0;
+            for (int i = skip + threadIdx.x; i < run * G; i += kWgThreads)
+                store_agent(&p.part_lse[slot * G + i], -INFINITY);
+        }
+
+        if (FUSED) {
+            // a7: the partial went out with coherent stores; once they are acknowledged
+            // and every wave has reached the barrier, one thread counts the run's splits
+            // as arrived (Algorithm 4: push, then atomic increment of the flag).
+            // a8: whoever completes the tile's count combines it.
+            wait_stores_done();
             __syncthreads();
             if (threadIdx.x == 0) {
-                const uint32_t old = atomicAdd(&p.counters[it.tile], 1u);
-                is_last = old == (uint32_t)(it.n - 1);
+                const uint32_t old = __hip_atomic_fetch_add(&p.counters[it.tile], (uint32_t)run, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                ss.is_last = old + (uint32_t)run == (uint32_t)it.n;
             }
             __syncthreads();
-            if (is_last) {
-                __threadfence();
-                combine_tile<G>(p, it.tile, it.b, it.kvh, it.n, sm.comb);
-                if (threadIdx.x == 0) p.counters[it.tile] = 0;     // re-arm for the next call
+            if (ss.is_last) {
+                combine_tile(p, it.tile, it.b, it.kvh, it.n, comb);
+                if (threadIdx.x == 0)                               // re-arm for the next call
+                    __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __syncthreads();
         }
     }
 }
 
-// Kernel 2 of the bulk-synchronous baseline: one workgroup per tile with more
-// than one split.
 template <int G>
+union __attribute__((aligned(16))) ValuWgSmem {
+    ItemSmem<G> item;
+    CombineSmem comb;
+};
+
+template <int G, bool FUSED>
+__global__ __launch_bounds__(kWgThreads, (G <= 5 ? 2 : 1)) void fd_valu_kernel(Params p)
+{
+    __shared__ ValuWgSmem<G> sm;
+    __shared__ SchedSmem ss;
+    persistent_loop<FUSED>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
+}
+
+extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
+
+template <int NST, bool FUSED>
+__global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
+{
+    static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
+    __shared__ SchedSmem ss;
+    persistent_loop<FUSED>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+}
+
+// Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
 __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
 {
-    __shared__ float sm[2 * G];
+    __shared__ CombineSmem sm;
+    __shared__ uint32_t done;
     const int tile = blockIdx.x;
     const int b = tile / p.Hkv, kvh = tile - b * p.Hkv;
     const int n = num_splits_of(p, seq_len_of(p, b));
-    if (n == 1) return;
-    combine_tile<G>(p, tile, b, kvh, n, sm);
+    // kernel 1 marks tiles it wrote as final results (all splits in one block)
+    if (threadIdx.x == 0) {
+        done = p.counters[tile];
+        if (done) p.counters[tile] = 0u;
+    }
+    __syncthreads();
+    if (done) return;
+    combine_tile(p, tile, b, kvh, n, sm);
 }
 
 }  // namespace fd
@@ -159,7 +230,7 @@ int check_config(const fd_config* c)
     if (c->D != fd::kD) return fail(FD_ERR_UNSUPPORTED, "only D = 128 is built (got %d)", c->D);
     if (c->kv_layout != 0) return fail(FD_ERR_UNSUPPORTED, "only kv_layout 0 ([B,Hkv,S_max,D]) is built");
     const int G = c->Hq / c->Hkv;
-    if (G > 8) return fail(FD_ERR_UNSUPPORTED, "GQA group Hq/Hkv = %d is not built (1..8)", G);
+    if (G > 16) return fail(FD_ERR_UNSUPPORTED, "GQA group Hq/Hkv = %d is not built (1..16)", G);
     if ((long long)c->B * c->Hkv > (1ll << 24)) return fail(FD_ERR_UNSUPPORTED, "B*Hkv too large");
     return FD_OK;
 }
@@ -182,22 +253,51 @@ int check_handle(fd_handle_t h)
     return FD_OK;
 }
 
+int launch_combine(const fd::Params& p, hipStream_t st)
+{
+    hipLaunchKernelGGL(fd::fd_combine_kernel, dim3(p.B * p.Hkv), dim3(fd::kWgThreads), 0, st, p);
+    FD_HIP(hipGetLastError());
+    return FD_OK;
+}
+
 template <int G>
-int launch_g(fd_handle_t h, const fd::Params& p, bool fused, int grid, hipStream_t st)
+int launch_valu(const fd::Params& p, bool fused, int grid, hipStream_t st)
 {
     if (fused) {
         hipLaunchKernelGGL((fd::fd_valu_kernel<G, true>), dim3(grid), dim3(fd::kWgThreads), 0, st, p);
         FD_HIP(hipGetLastError());
-    } else {
-        hipLaunchKernelGGL((fd::fd_valu_kernel<G, false>), dim3(grid), dim3(fd::kWgThreads), 0, st, p);
-        FD_HIP(hipGetLastError());
-        if (p.n_splits != 1) {
-            hipLaunchKernelGGL((fd::fd_combine_kernel<G>), dim3(p.B * p.Hkv), dim3(fd::kWgThreads), 0, st, p);
-            FD_HIP(hipGetLastError());
-        }
+        return FD_OK;
     }
-    h->last_path = 1;
-    return FD_OK;
+    hipLaunchKernelGGL((fd::fd_valu_kernel<G, false>), dim3(grid), dim3(fd::kWgThreads), 0, st, p);
+    FD_HIP(hipGetLastError());
+    return launch_combine(p, st);
+}
+
+template <int NST>
+int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
+{
+    // more than 64 KB of dynamic LDS has to be granted once per kernel and device
+    static thread_local int granted_device[2] = {-1, -1};
+    int dev = 0;
+    FD_HIP(hipGetDevice(&dev));
+    const size_t ring = (size_t)fd::mfma_ring_bytes(NST);
+    if (granted_device[fused] != dev) {
+        if (fused)
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
+        else
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
+        granted_device[fused] = dev;
+    }
+    if (fused) {
+        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+        FD_HIP(hipGetLastError());
+        return FD_OK;
+    }
+    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+    FD_HIP(hipGetLastError());
+    return launch_combine(p, st);
 }
 
 int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, const int32_t* seq_lens, float* out,
@@ -213,9 +313,18 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     const fd_config& c = h->cfg;
     const int tiles = c.B * c.Hkv;
 
-    // persistent grid: a fixed number of workgroups per CU, never more than there are items
+    // which kernel: matrix cores when the GQA group fills at least half an MFMA tile
+    const int G = h->G;
+    int path = h->opt_path;
+    if (path == 0) path = G >= 8 ? 2 : 1;
+    if (path == 1 && G > 8) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for Hq/Hkv <= 8 (got %d)", G);
+
+    // persistent grid: a fixed number of workgroups per CU, never more than there are items.
+    // The MFMA kernel trades ring depth for residency: 1 workgroup per CU with 4 stages
+    // per wave, or 2 per CU with 2 stages.
     const long long items_max = (long long)tiles * (n_splits > 0 ? n_splits : c.max_splits);
-    const int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : 2;
+    int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : (path == 2 ? 1 : 2);
+    if (path == 2 && per_cu > 2) per_cu = 2;
     long long grid = (long long)h->num_cus * per_cu;
     if (grid > items_max) grid = items_max;
     int X = h->opt_xcd;
@@ -245,16 +354,18 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
 
     hipStream_t st = (hipStream_t)stream;
     h->last_grid = (int)grid;
-    switch (h->G) {
-        case 1: return launch_g<1>(h, p, fused, (int)grid, st);
-        case 2: return launch_g<2>(h, p, fused, (int)grid, st);
-        case 3: return launch_g<3>(h, p, fused, (int)grid, st);
-        case 4: return launch_g<4>(h, p, fused, (int)grid, st);
-        case 5: return launch_g<5>(h, p, fused, (int)grid, st);
-        case 6: return launch_g<6>(h, p, fused, (int)grid, st);
-        case 7: return launch_g<7>(h, p, fused, (int)grid, st);
-        case 8: return launch_g<8>(h, p, fused, (int)grid, st);
-        default: return fail(FD_ERR_UNSUPPORTED, "GQA group %d is not built", h->G);
+    h->last_path = path;
+    if (path == 2) return per_cu == 1 ? launch_mfma<4>(p, fused, (int)grid, st) : launch_mfma<2>(p, fused, (int)grid, st);
+    switch (G) {
+        case 1: return launch_valu<1>(p, fused, (int)grid, st);
+        case 2: return launch_valu<2>(p, fused, (int)grid, st);
+        case 3: return launch_valu<3>(p, fused, (int)grid, st);
+        case 4: return launch_valu<4>(p, fused, (int)grid, st);
+        case 5: return launch_valu<5>(p, fused, (int)grid, st);
+        case 6: return launch_valu<6>(p, fused, (int)grid, st);
+        case 7: return launch_valu<7>(p, fused, (int)grid, st);
+        case 8: return launch_valu<8>(p, fused, (int)grid, st);
+        default: return fail(FD_ERR_UNSUPPORTED, "GQA group %d is not built", G);
     }
 }
 

@@ -1,0 +1,261 @@
+// Partial attention of one key range on the matrix cores (GQA group >= 8: the
+// group's query rows fill at least half of a 16-row MFMA tile).
+//
+// Steps a2-a6 of the hot path (paper Section 4.2.1, Algorithm 4 Part 1) for up
+// to 16 query heads that share one KV head.
+//
+// Data flow, per wave (the 4 waves of a workgroup are independent pipelines):
+//   * K and V rows go global -> LDS directly (global_load_lds_dwordx4, no
+//     registers in between).  The wave owns a private ring of NST stages in LDS,
+//     one stage = 16 keys of K (4 KB) + the same 16 keys of V (4 KB), and keeps
+//     NST-1 stages in flight while it computes on the oldest.  A wave only reads
+//     what it loaded itself, so the loop needs no workgroup barrier: the wave's
+//     own vmcnt tells it when a stage has landed.
+//   * wave w takes the 16-key blocks w, w+4, w+8, ... of the range, so the
+//     workgroup streams the range front to back.
+//   * QK^T: S^T[16 keys x 16 heads] = K_blk . q^T with 4 v_mfma_f32_16x16x32_bf16
+//     (contraction over D = 128).  K is the A operand, read from LDS as 16-byte
+//     chunks (one chunk = 8 dims); rows are XOR-swizzled so the 16 rows of a
+//     block hit 16 different chunk positions.
+//   * the result layout (lane = head, 4 keys per lane) is exactly the B operand
+//     layout of v_mfma_f32_16x16x16_bf16, so P never moves between lanes.
+//   * P is split into bf16 hi + lo parts (p = hi + lo to 2^-16 relative), two
+//     MFMAs per 16-dim block, so the result carries fp32-grade weights.
+//   * PV: O^T[16 dims x 16 heads] += V^T_blk . P^T; the transposed V operand comes
+//     from ds_read_b64_tr_b16, which hands each lane 4 keys of one dim.
+#pragma once
+
+#include "fd_device.hpp"
+
+namespace fd {
+
+constexpr int kMfBlockKeys = 16;                            // keys per wave stage
+constexpr int kMfHalfBytes = kMfBlockKeys * kD * 2;         // K (or V) of a stage: 4 KB
+constexpr int kMfStageBytes = 2 * kMfHalfBytes;             // 8 KB
+constexpr int kMfRows = 16;                                 // MFMA tile rows = max heads per KV head
+
+__host__ __device__ constexpr int mfma_ring_bytes(int nst) { return kWaves * nst * kMfStageBytes; }
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+
+// 64 lanes x 16 bytes, global -> LDS.  Lane l's 16 bytes come from gbase + voff(l)
+// and land at LDS byte address lds_addr + 16*l.  lds_addr and gbase are
+// wave-uniform.  Completion is tracked by vmcnt like any vector load.
+__device__ __forceinline__ void dma_row4(uint32_t lds_addr, const void* gbase, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// waits until at most `stages` later stages (8 loads each) are still in flight
+__device__ __forceinline__ void wait_stages_in_flight(int stages)
+{
+    switch (stages) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<8>(); break;
+        case 2: wait_vmcnt<16>(); break;
+        case 3: wait_vmcnt<24>(); break;
+        case 4: wait_vmcnt<32>(); break;
+        case 5: wait_vmcnt<40>(); break;
+        case 6: wait_vmcnt<48>(); break;
+        default: wait_vmcnt<56>(); break;
+    }
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+struct MfmaState {
+    float m;            // running max of head (lane & 15), base-2 units, same in the 4 lanes of a head
+    float l;            // this lane's share of the running sum (its 4 keys per block)
+    f32x4_t acc[8];     // O^T: block db, element e = dim 16*db + 4*(lane>>4) + e of head (lane & 15)
+};
+
+// Requests the 16 keys [kb, kb+16) of K and V into one stage.  Rows at or past
+// j1 re-read row j1-1 (a live row); their scores are masked later.
+// LDS layout of a half stage: row r (0..15) at r*256, its 16-byte chunk c stored at
+// position c ^ r.
+__device__ __forceinline__ void mfma_issue_stage(uint32_t lds_stage, const uint16_t* kbase, const uint16_t* vbase,
+                                                 int kb, int j1, int lane)
+{
+    const int rsub = lane >> 4, pos = lane & 15;
+    const bool full = kb + kMfBlockKeys <= j1;
+    const uint16_t* kp = kbase + (size_t)kb * kD;
+    const uint16_t* vp = vbase + (size_t)kb * kD;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 4 * i + rsub;                       // row of the block this lane fills
+        int src_row = r;
+        if (!full) src_row = min(r, j1 - 1 - kb);
+        const uint32_t voff = (uint32_t)(src_row * 256 + ((pos ^ r) << 4));
+        dma_row4(lds_stage + i * 1024, kp, voff);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 4 * i + rsub;
+        int src_row = r;
+        if (!full) src_row = min(r, j1 - 1 - kb);
+        const uint32_t voff = (uint32_t)(src_row * 256 + ((pos ^ r) << 4));
+        dma_row4(lds_stage + kMfHalfBytes + i * 1024, vp, voff);
+    }
+}
+
+// One landed stage: scores, online softmax, PV.
+template <bool MASKED>
+__device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16x8_t (&qb)[4], MfmaState& st,
+                                                   float scale_log2, int kb, int j1, int lane)
+{
+    const int i16 = lane & 15, kg = lane >> 4;
+
+    // a3: S^T[key i16][head] over D = 4 steps of 32 dims; step t, lane group kg uses chunk 4t + kg
+    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int chunk = 4 * t + kg;
+        const uint4 kk = *reinterpret_cast<const uint4*>(stage + i16 * 256 + ((chunk ^ i16) << 4));
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kk), qb[t], s, 0, 0, 0);
+    }
+    // now s[e] = <q_head, K[kb + 4kg + e]> for head = lane & 15
+
+    // a4: online softmax in base 2
+    float p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        p[e] = s[e] * scale_log2;
+        if (MASKED) p[e] = (kb + 4 * kg + e) < j1 ? p[e] : -INFINITY;
+    }
+    float tm = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3]));
+    tm = fmaxf(tm, __shfl_xor(tm, 16));
+    tm = fmaxf(tm, __shfl_xor(tm, 32));
+    const float mnew = fmaxf(st.m, tm);
+    if (__any(mnew > st.m)) {
+        const float alpha = fast_exp2(st.m - mnew);
+        st.m = mnew;
+        st.l *= alpha;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) st.acc[db] *= alpha;
+    }
+    s16x4_t phi, plo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        p[e] = fast_exp2(p[e] - st.m);
+        st.l += p[e];
+        const __bf16 hi = (__bf16)p[e];
+        const __bf16 lo = (__bf16)(p[e] - (float)hi);
+        phi[e] = __builtin_bit_cast(short, hi);
+        plo[e] = __builtin_bit_cast(short, lo);
+    }
+
+    // a5: O^T[dim][head] += V^T . P^T, 16 dims at a time.  Lane t of a 16-lane group
+    // points at row 4kg + t/4, dims 16db + 4(t%4) .. +3; the transposing read then
+    // gives lane i the 4 keys 4kg..4kg+3 of dim 16db + i.
+    const char* vstage = stage + kMfHalfBytes;
+    const int vrow = 4 * kg + (i16 >> 2);
+    const int vsub = i16 & 3;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+        const int chunk = 2 * db + (vsub >> 1);
+        const char* src = vstage + vrow * 256 + ((chunk ^ vrow) << 4) + ((vsub & 1) << 3);
+        const s16x4_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)src);
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, phi, st.acc[db], 0, 0, 0);
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, plo, st.acc[db], 0, 0, 0);
+    }
+}
+
+// Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) for its G <= 16 query heads.
+// ring: this workgroup's LDS ring (mfma_ring_bytes(NST) bytes, 16-byte aligned);
+// it doubles as the ItemSmem<16> staging at the end of the range.
+// Writes the normalised result to dst_o[G][D] and the log-sum-exp times lse_mul to
+// dst_lse[G] (SHARED as in item_finish).  Leaves LDS free for reuse on return.
+template <int NST, bool SHARED>
+__device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
+                                 float lse_mul, char* ring)
+{
+    static_assert(NST >= 2 && NST <= 8, "ring depth");
+    static_assert(sizeof(ItemSmem<kMfRows>) <= (size_t)mfma_ring_bytes(2), "staging must fit the ring");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int G = p.G;
+    const int head = lane & 15, kg = lane >> 4;
+
+    // a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero
+    bf16x8_t qb[4];
+    {
+        const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * G + head) * kRowU4;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (head < G) v = qp[4 * t + kg];
+            qb[t] = __builtin_bit_cast(bf16x8_t, v);
+        }
+        // Make the compiler wait for these loads HERE.  The loop below must contain no
+        // compiler-generated vmcnt wait: such a wait would also drain the stage loads the
+        // loop keeps in flight (they are issued from inline asm, invisible to its counter).
+        asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
+    }
+    const size_t row0 = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
+    const uint16_t* kbase = p.k + row0 * kD;
+    const uint16_t* vbase = p.v + row0 * kD;
+
+    MfmaState st;
+    st.m = kNegBig;
+    st.l = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) st.acc[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // a3-a5: this wave's blocks are wave, wave + 4, ...; `mine` of them
+    const int n_blocks = (j1 - j0 + kMfBlockKeys - 1) / kMfBlockKeys;
+    const int mine = wave < n_blocks ? (n_blocks - wave + kWaves - 1) / kWaves : 0;
+    char* my_ring = ring + wave * (NST * kMfStageBytes);
+    const uint32_t my_ring_lds = lds_address(my_ring);
+    const float sl2 = p.scale_log2;
+    constexpr int P = NST - 1;                            // stages in flight ahead of the one being consumed
+
+    for (int s = 0; s < P && s < mine; ++s)
+        mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kbase, vbase, j0 + (wave + kWaves * s) * kMfBlockKeys, j1,
+                         lane);
+    for (int s = 0; s < mine; ++s) {
+        if (s + P < mine)
+            mfma_issue_stage(my_ring_lds + ((s + P) % NST) * kMfStageBytes, kbase, vbase,
+                             j0 + (wave + kWaves * (s + P)) * kMfBlockKeys, j1, lane);
+        wait_stages_in_flight(min(P, mine - 1 - s));
+        const int kb = j0 + (wave + kWaves * s) * kMfBlockKeys;
+        const char* stage = my_ring + (s % NST) * kMfStageBytes;
+        if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
+        else mfma_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+    }
+
+    // a6: every lane of a head gets the head's sum; then the wave leaves its state in LDS
+    st.l += __shfl_xor(st.l, 16);
+    st.l += __shfl_xor(st.l, 32);
+    __syncthreads();                                      // all waves are done reading their rings
+    ItemSmem<kMfRows>& sm = *reinterpret_cast<ItemSmem<kMfRows>*>(ring);
+    if (head < G) {
+        if (kg == 0) {
+            sm.m[wave][head] = st.m;
+            sm.l[wave][head] = st.l;
+        }
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+            *reinterpret_cast<float4*>(&sm.acc[wave][head][16 * db + 4 * kg]) =
+                make_float4(st.acc[db][0], st.acc[db][1], st.acc[db][2], st.acc[db][3]);
+    }
+    __syncthreads();
+    item_finish<kMfRows, SHARED>(sm, G, dst_o, dst_lse, lse_mul);
+}
+
+}  // namespace fd

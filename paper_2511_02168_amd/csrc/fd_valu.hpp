@@ -25,13 +25,6 @@ namespace fd {
 constexpr int kValuTileKeys = 32;   // keys per wave tile (8 loads x 4 rows)
 constexpr int kValuLoads = kValuTileKeys / 4;
 
-template <int G>
-struct ValuSmem {
-    float m[kWaves][G];
-    float l[kWaves][G];
-    float acc[kWaves][G][kD];
-};
-
 // Loads keys kb + 4*i + r (i = 0..7) of K or of V.  MASKED: rows at or past j1
 // re-read row j1-1 (always a live row); their scores are forced to -inf later.
 template <bool MASKED>
@@ -41,7 +34,7 @@ __device__ __forceinline__ void valu_load_rows(uint4 (&dst)[kValuLoads], const u
     for (int i = 0; i < kValuLoads; ++i) {
         int key = kb + 4 * i + r;
         if (MASKED) key = key < j1 ? key : j1 - 1;
-        dst[i] = base[(size_t)key * kRowU4 + c];
+        dst[i] = load_stream(base + (size_t)key * kRowU4 + c);
     }
 }
 
@@ -135,10 +128,12 @@ __device__ __forceinline__ void valu_pv(const uint4 (&vt)[kValuLoads], const flo
 
 // Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) for its G query heads and
 // writes the normalised result to dst_o[G][D] and (if non-null) the log-sum-exp
-// times lse_mul to dst_lse[G].  Leaves LDS free for reuse on return.
-template <int G>
+// times lse_mul to dst_lse[G].  SHARED: the destination is a partial that another
+// workgroup may read within this launch (coherent stores).  Leaves LDS free for
+// reuse on return.
+template <int G, bool SHARED>
 __device__ inline void valu_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
-                                 float lse_mul, ValuSmem<G>& sm)
+                                 float lse_mul, ItemSmem<G>& sm)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -231,23 +226,7 @@ __device__ inline void valu_item(const Params& p, int b, int kvh, int j0, int j1
     }
     __syncthreads();
 
-    // merge the 4 waves, normalise, store
-    for (int idx = tid; idx < G * kD; idx += kWgThreads) {
-        const int g = idx / kD, d = idx % kD;
-        float M = sm.m[0][g];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm.m[w][g]);
-        float L = 0.f, o = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float f = fast_exp2(sm.m[w][g] - M);
-            L += sm.l[w][g] * f;
-            o += sm.acc[w][g][d] * f;
-        }
-        dst_o[idx] = o / L;
-        if (d == 0 && dst_lse) dst_lse[g] = (M + fast_log2(L)) * lse_mul;
-    }
-    __syncthreads();
+    item_finish<G, SHARED>(sm, G, dst_o, dst_lse, lse_mul);
 }
 
 }  // namespace fd

@@ -56,7 +56,7 @@ def test_workspace_bytes_formula():
     (dict(scale=float("nan")), fd.FD_ERR_INVALID_ARG),
     (dict(D=64), fd.FD_ERR_UNSUPPORTED),
     (dict(kv_layout=1), fd.FD_ERR_UNSUPPORTED),
-    (dict(Hq=64, Hkv=2), fd.FD_ERR_UNSUPPORTED),
+    (dict(Hq=68, Hkv=2), fd.FD_ERR_UNSUPPORTED),
 ])
 def test_create_rejects_bad_config_before_touching_the_device(kw, code):
     with pytest.raises(fd.FdError) as e:
