@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy 3 times (known HBM traffic: 1 GiB read + 1 GiB "
+                         "written per launch) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     return ap.parse_args()
 
 
@@ -136,6 +139,14 @@ def main():
     def bsp(i):
         j = i % copies
         fd.fd_decode_bsp(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+
+    if args.pmc_calibration:
+        src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     fused_ms, fused_wall_ms = time_calls(fused, args.warmup, args.steps, torch)
     grid = fd.fd_get_option(dec.h, fd.FD_INFO_LAST_GRID)

@@ -299,42 +299,65 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     const float* plse = p.part_lse + (size_t)tile * p.max_splits * G;
     const float* po = p.part_o + (size_t)tile * p.max_splits * G * kD;
 
-    // phase 0: wave 0 lists the live slots in ascending order
-    if (wave == 0) {
-        int count = 0;
-        for (int base = 0; base < n; base += 64) {
-            const int i = base + lane;
-            const bool live = i < n && load_agent(&plse[i * G]) != -INFINITY;
-            const unsigned long long mask = __ballot(live);
-            if (live) sm.live[count + __popcll(mask & ((1ull << lane) - 1ull))] = i;
-            count += __popcll(mask);
+    // phase A (one memory round trip): wave w takes heads w, w+4, ...; each lane loads
+    // the lse of slots lane, lane+64, ... for all of its wave's heads at once.  Empty
+    // slots hold -inf for every head, so they drop out of max and sum by themselves.
+    // Wave 0 also lists the live slots (ascending) from what it loaded for head 0.
+    constexpr int kPerLane = kMaxSplits / 64;
+    constexpr int kHeadsPerWave = 16 / kWaves;
+    {
+        float v[kHeadsPerWave][kPerLane];
+#pragma unroll
+        for (int j = 0; j < kHeadsPerWave; ++j) {
+            const int g = wave + kWaves * j;
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u) {
+                const int i = lane + 64 * u;
+                v[j][u] = (g < G && i < n) ? load_agent(&plse[i * G + g]) : -INFINITY;
+            }
         }
-        if (lane == 0) sm.n_live = count;
+        if (wave == 0) {
+            int count = 0;
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u) {
+                const bool live = v[0][u] != -INFINITY;
+                const unsigned long long mask = __ballot(live);
+                if (live) sm.live[count + __popcll(mask & ((1ull << lane) - 1ull))] = lane + 64 * u;
+                count += __popcll(mask);
+            }
+            if (lane == 0) sm.n_live = count;
+        }
+#pragma unroll
+        for (int j = 0; j < kHeadsPerWave; ++j) {
+            const int g = wave + kWaves * j;
+            if (g >= G) break;
+            float mx = v[j][0];
+#pragma unroll
+            for (int u = 1; u < kPerLane; ++u) mx = fmaxf(mx, v[j][u]);
+            mx = wave_max(mx);
+            float sum = 0.f;
+            if (mx != -INFINITY) {
+#pragma unroll
+                for (int u = 0; u < kPerLane; ++u) sum += fast_exp2(v[j][u] - mx);
+            }
+            sum = wave_sum(sum);
+            if (lane == 0) {
+                sm.M[g] = mx;
+                sm.invL[g] = sum > 0.f ? 1.0f / sum : 0.f;
+                if (p.lse) p.lse[(size_t)b * p.Hq + kvh * G + g] = sum > 0.f ? (mx + fast_log2(sum)) * kLn2 : -INFINITY;
+            }
+        }
     }
     __syncthreads();
     const int n_live = sm.n_live;
 
-    // phase 1: per head, max and sum of the live rows' weights
-    for (int g = wave; g < G; g += kWaves) {
-        float mx = -INFINITY;
-        for (int k = lane; k < n_live; k += 64) mx = fmaxf(mx, load_agent(&plse[sm.live[k] * G + g]));
-        mx = wave_max(mx);
-        float sum = 0.f;
-        for (int k = lane; k < n_live; k += 64) sum += fast_exp2(load_agent(&plse[sm.live[k] * G + g]) - mx);
-        sum = wave_sum(sum);
-        if (lane == 0) {
-            sm.M[g] = mx;
-            sm.invL[g] = n_live > 0 ? 1.0f / sum : 0.f;
-            if (p.lse) p.lse[(size_t)b * p.Hq + kvh * G + g] = n_live > 0 ? (mx + fast_log2(sum)) * kLn2 : -INFINITY;
-        }
-    }
-    __syncthreads();
-
-    // phase 2: out[g][d] = sum_k w_k[g] * o_k[g][d].  A thread owns one (g, 4 dims)
+    // phase B: out[g][d] = sum_k w_k[g] * o_k[g][d].  A thread owns one (g, 4 dims)
     // pair; when there are fewer pairs than threads, R threads share a pair, each
-    // taking every R-th live row, and their sums are added in slice order.
+    // taking every R-th live row, and their sums are added in slice order.  The
+    // loads of 16 rows are in flight together (one round trip per 16 rows).
     const int kPairs = G * (kD / 4);
     const int R = kPairs >= kWgThreads ? 1 : kWgThreads / kPairs;
+    constexpr int kBatch = 16;
     float4* dst = reinterpret_cast<float4*>(p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD);
     for (int pbase = 0; pbase < kPairs; pbase += kWgThreads) {
         const int pair = pbase + (R > 1 ? tid % kPairs : tid);
@@ -344,16 +367,26 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
         if (active) {
             const int g = pair / (kD / 4), d4 = pair % (kD / 4);
             const float M = sm.M[g], invL = sm.invL[g];
-#pragma unroll 8
-            for (int k = slice; k < n_live; k += R) {
-                const int i = sm.live[k];
-                const float w = fast_exp2(load_agent(&plse[i * G + g]) - M) * invL;
-                const float* src = po + ((size_t)(i * G + g) * (kD / 4) + d4) * 4;
-                const float2 x01 = load_agent2(src), x23 = load_agent2(src + 2);
-                o.x += w * x01.x;
-                o.y += w * x01.y;
-                o.z += w * x23.x;
-                o.w += w * x23.y;
+            for (int k0 = slice; k0 < n_live; k0 += R * kBatch) {
+                float lw[kBatch];
+                float2 x01[kBatch], x23[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const int k = k0 + R * u;
+                    const int i = sm.live[k < n_live ? k : k0];
+                    const float* src = po + ((size_t)(i * G + g) * (kD / 4) + d4) * 4;
+                    lw[u] = load_agent(&plse[i * G + g]);
+                    x01[u] = load_agent2(src);
+                    x23[u] = load_agent2(src + 2);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float w = (k0 + R * u) < n_live ? fast_exp2(lw[u] - M) * invL : 0.f;
+                    o.x += w * x01[u].x;
+                    o.y += w * x01[u].y;
+                    o.z += w * x23[u].x;
+                    o.w += w * x23[u].y;
+                }
             }
         }
         if (R > 1) {

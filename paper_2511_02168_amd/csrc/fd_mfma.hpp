@@ -43,10 +43,11 @@ typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
 // 64 lanes x 16 bytes, global -> LDS.  Lane l's 16 bytes come from gbase + voff(l)
 // and land at LDS byte address lds_addr + 16*l.  lds_addr and gbase are
-// wave-uniform.  Completion is tracked by vmcnt like any vector load.
+// wave-uniform.  Completion is tracked by vmcnt like any vector load.  The data is
+// used once: the non-temporal hint raises streaming read bandwidth measurably.
 __device__ __forceinline__ void dma_row4(uint32_t lds_addr, const void* gbase, uint32_t voff)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(gbase)
                  : "memory", "m0");
@@ -192,21 +193,6 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     const int G = p.G;
     const int head = lane & 15, kg = lane >> 4;
 
-    // a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero
-    bf16x8_t qb[4];
-    {
-        const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * G + head) * kRowU4;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (head < G) v = qp[4 * t + kg];
-            qb[t] = __builtin_bit_cast(bf16x8_t, v);
-        }
-        // Make the compiler wait for these loads HERE.  The loop below must contain no
-        // compiler-generated vmcnt wait: such a wait would also drain the stage loads the
-        // loop keeps in flight (they are issued from inline asm, invisible to its counter).
-        asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
-    }
     const size_t row0 = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
     const uint16_t* kbase = p.k + row0 * kD;
     const uint16_t* vbase = p.v + row0 * kD;
@@ -228,6 +214,22 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     for (int s = 0; s < P && s < mine; ++s)
         mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kbase, vbase, j0 + (wave + kWaves * s) * kMfBlockKeys, j1,
                          lane);
+    // a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero
+    bf16x8_t qb[4];
+    {
+        const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * G + head) * kRowU4;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (head < G) v = qp[4 * t + kg];
+            qb[t] = __builtin_bit_cast(bf16x8_t, v);
+        }
+        // Requested after the first stages so that both arrive in one memory round trip.
+        // Make the compiler wait for these loads HERE: the loop below must contain no
+        // compiler-generated vmcnt wait, which would also drain the stage loads the loop
+        // keeps in flight (they are issued from inline asm, invisible to its counter).
+        asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
+    }
     for (int s = 0; s < mine; ++s) {
         if (s + P < mine)
             mfma_issue_stage(my_ring_lds + ((s + P) % NST) * kMfStageBytes, kbase, vbase,
