@@ -155,6 +155,17 @@ int fd_debug_poison_workspace(fd_handle_t h, void* stream);
 /* Test aid: copies the arrival counters to host memory (synchronous); n = B*Hkv. */
 int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n);
 
+/*
+ * Tuning aid: attaches (or, with NULL, detaches) a device buffer of
+ * capacity_workgroups * FD_TRACE_EVENTS uint64 in which every workgroup of later
+ * fused / split launches records 100 MHz timestamps of its milestones (start, first
+ * stage landed, loop end, partial stored, stores acknowledged, counted, combined,
+ * end; the last key range of the workgroup wins).  Launches with more workgroups
+ * than the capacity record nothing.  The caller owns the buffer.
+ */
+#define FD_TRACE_EVENTS 8
+int fd_debug_set_trace(fd_handle_t h, void* device_buffer, int32_t capacity_workgroups);
+
 /* Text of the calling thread's last error ("" if none). Never NULL. */
 const char* fd_last_error(void);
 int fd_version(void);

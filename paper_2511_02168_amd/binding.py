@@ -21,6 +21,7 @@ FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH = 100, 101, 102
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
            "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
+           "fd_debug_set_trace",
            "fd_last_error", "fd_version"]
 
 
@@ -68,6 +69,8 @@ def lib():
         L.fd_debug_poison_workspace.argtypes = [vp, vp]
         L.fd_debug_read_counters.restype = ctypes.c_int
         L.fd_debug_read_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), i32]
+        L.fd_debug_set_trace.restype = ctypes.c_int
+        L.fd_debug_set_trace.argtypes = [vp, vp, i32]
         L.fd_last_error.restype = ctypes.c_char_p
         L.fd_last_error.argtypes = []
         L.fd_version.restype = ctypes.c_int
@@ -139,6 +142,13 @@ def fd_debug_read_counters(h, n: int):
     buf = (ctypes.c_uint32 * n)()
     _check(lib().fd_debug_read_counters(h, buf, n))
     return list(buf)
+
+
+FD_TRACE_EVENTS = 8
+
+
+def fd_debug_set_trace(h, buf, capacity_workgroups: int) -> None:
+    _check(lib().fd_debug_set_trace(h, _ptr(buf), int(capacity_workgroups)))
 
 
 class FlashDecode:

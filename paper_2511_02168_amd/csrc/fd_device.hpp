@@ -40,7 +40,17 @@ struct Params {
     int32_t max_splits;
     int32_t xcd_groups;       // 1 or 8
     float scale_log2;         // softmax scale * log2(e)
+    unsigned long long* trace;  // optional [grid][kTraceEvents] timestamps (100 MHz), or null
 };
+
+// ---- optional in-kernel timeline (for tuning; off unless a buffer is attached) --
+constexpr int kTraceEvents = 8;
+enum { kEvStart = 0, kEvFirstStage = 1, kEvLoopEnd = 2, kEvPartialOut = 3, kEvStoresAcked = 4, kEvCounted = 5,
+       kEvCombined = 6, kEvEnd = 7 };
+__device__ __forceinline__ void trace_event(const Params& p, int ev)
+{
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * kTraceEvents + ev] = wall_clock64();
+}
 
 // Sequence length as the kernels use it: clamped into [0, S_max] so that a bad
 // entry can never index outside the cache.

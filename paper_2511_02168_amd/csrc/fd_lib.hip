@@ -59,6 +59,7 @@ template <bool FUSED, class Path>
 __device__ __forceinline__ void persistent_loop(const Params& p, const Path& path, SchedSmem& ss, CombineSmem& comb)
 {
     const int G = p.G;
+    trace_event(p, kEvStart);
     WorkList wl;
     worklist_init(p, wl, ss.pre, ss.scan_tmp);
 
@@ -105,12 +106,14 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
                 store_agent(&p.part_lse[slot * G + i], -INFINITY);
         }
 
+        trace_event(p, kEvPartialOut);
         if (FUSED) {
             // a7: the partial went out with coherent stores; once they are acknowledged
             // and every wave has reached the barrier, one thread counts the run's splits
             // as arrived (Algorithm 4: push, then atomic increment of the flag).
             // a8: whoever completes the tile's count combines it.
             wait_stores_done();
+            trace_event(p, kEvStoresAcked);
             __syncthreads();
             if (threadIdx.x == 0) {
                 const uint32_t old = __hip_atomic_fetch_add(&p.counters[it.tile], (uint32_t)run, __ATOMIC_RELAXED,
@@ -118,14 +121,17 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
                 ss.is_last = old + (uint32_t)run == (uint32_t)it.n;
             }
             __syncthreads();
+            trace_event(p, kEvCounted);
             if (ss.is_last) {
                 combine_tile(p, it.tile, it.b, it.kvh, it.n, comb);
                 if (threadIdx.x == 0)                               // re-arm for the next call
                     __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                trace_event(p, kEvCombined);
             }
             __syncthreads();
         }
     }
+    trace_event(p, kEvEnd);
 }
 
 template <int G>
@@ -213,6 +219,8 @@ struct fd_handle_s {
     Layout lay;
     int opt_path, opt_xcd, opt_wgs_per_cu;
     int last_grid, last_path;
+    unsigned long long* trace;
+    int trace_capacity;      // workgroups the trace buffer has room for
 };
 
 namespace {
@@ -351,6 +359,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.xcd_groups = X;
     const float scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.D);
     p.scale_log2 = scale * 1.4426950408889634f;
+    p.trace = (h->trace && grid <= h->trace_capacity) ? h->trace : nullptr;
 
     hipStream_t st = (hipStream_t)stream;
     h->last_grid = (int)grid;
@@ -401,6 +410,8 @@ int fd_create(const fd_config* cfg, fd_handle_t* out)
     h->lay = make_layout(*cfg);
     h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = 0;
     h->last_grid = h->last_path = 0;
+    h->trace = nullptr;
+    h->trace_capacity = 0;
     hipError_t e = hipMalloc(&h->workspace, h->lay.total);
     if (e != hipSuccess) {
         const size_t want = h->lay.total;
@@ -504,6 +515,17 @@ int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n)
     FD_HIP(hipDeviceSynchronize());
     FD_HIP(hipMemcpy(host_dst, (char*)h->workspace + h->lay.counters_off, (size_t)n * sizeof(uint32_t),
                      hipMemcpyDeviceToHost));
+    return FD_OK;
+}
+
+int fd_debug_set_trace(fd_handle_t h, void* device_buffer, int32_t capacity_workgroups)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (device_buffer && capacity_workgroups <= 0) return fail(FD_ERR_INVALID_ARG, "trace capacity must be positive");
+    if ((uintptr_t)device_buffer & 7) return fail(FD_ERR_INVALID_ARG, "trace buffer must be 8-byte aligned");
+    h->trace = (unsigned long long*)device_buffer;
+    h->trace_capacity = device_buffer ? capacity_workgroups : 0;
     return FD_OK;
 }
 

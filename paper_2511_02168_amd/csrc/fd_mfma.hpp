@@ -235,12 +235,14 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             mfma_issue_stage(my_ring_lds + ((s + P) % NST) * kMfStageBytes, kbase, vbase,
                              j0 + (wave + kWaves * (s + P)) * kMfBlockKeys, j1, lane);
         wait_stages_in_flight(min(P, mine - 1 - s));
+        if (s == 0) trace_event(p, kEvFirstStage);
         const int kb = j0 + (wave + kWaves * s) * kMfBlockKeys;
         const char* stage = my_ring + (s % NST) * kMfStageBytes;
         if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
         else mfma_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
     }
 
+    trace_event(p, kEvLoopEnd);
     // a6: every lane of a head gets the head's sum; then the wave leaves its state in LDS
     st.l += __shfl_xor(st.l, 16);
     st.l += __shfl_xor(st.l, 32);

@@ -193,6 +193,7 @@ __device__ inline void valu_item(const Params& p, int b, int kvh, int j0, int j1
         t = tn;
     }
 
+    trace_event(p, kEvLoopEnd);
     // a6: merge the 4 row states of the wave (lanes c, c+16, c+32, c+48 hold the same dims)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
