@@ -129,7 +129,7 @@ int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void*
 
 /*
  * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.
- *   FD_OPT_PATH          0 auto (MFMA kernel when Hq/Hkv >= 8, VALU kernel below),
+ *   FD_OPT_PATH          0 auto (MFMA kernel when Hq/Hkv >= 4, VALU kernel below),
  *                        1 force VALU (Hq/Hkv <= 8 only), 2 force MFMA
  *   FD_OPT_XCD_GROUPS    0 auto, 1 = one global item list, 8 = items of a tile
  *                        stay on one XCD (tile t -> workgroups with id % 8 == t % 8)

@@ -301,6 +301,9 @@ struct CombineSmem {
     float4 red[kWgThreads];     // cross-slice reduction
 };
 
+// HEADS_PER_WAVE >= ceil(G / 4); BATCH = rows whose loads a thread keeps in flight together.
+// Both only bound the registers this one-off code may claim inside a kernel.
+template <int HEADS_PER_WAVE, int BATCH>
 __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm)
 {
     const int G = p.G;          // <= 16
@@ -314,7 +317,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     // slots hold -inf for every head, so they drop out of max and sum by themselves.
     // Wave 0 also lists the live slots (ascending) from what it loaded for head 0.
     constexpr int kPerLane = kMaxSplits / 64;
-    constexpr int kHeadsPerWave = 16 / kWaves;
+    constexpr int kHeadsPerWave = HEADS_PER_WAVE;
     {
         float v[kHeadsPerWave][kPerLane];
 #pragma unroll
@@ -367,7 +370,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     // loads of 16 rows are in flight together (one round trip per 16 rows).
     const int kPairs = G * (kD / 4);
     const int R = kPairs >= kWgThreads ? 1 : kWgThreads / kPairs;
-    constexpr int kBatch = 16;
+    constexpr int kBatch = BATCH;
     float4* dst = reinterpret_cast<float4*>(p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD);
     for (int pbase = 0; pbase < kPairs; pbase += kWgThreads) {
         const int pair = pbase + (R > 1 ? tid % kPairs : tid);
