@@ -158,12 +158,14 @@ int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n);
 /*
  * Tuning aid: attaches (or, with NULL, detaches) a device buffer of
  * capacity_workgroups * FD_TRACE_EVENTS uint64 in which every workgroup of later
- * fused / split launches records 100 MHz timestamps of its milestones (start, first
- * stage landed, loop end, partial stored, stores acknowledged, counted, combined,
- * end; the last key range of the workgroup wins).  Launches with more workgroups
- * than the capacity record nothing.  The caller owns the buffer.
+ * fused / split launches records 100 MHz timestamps of its milestones: 0 start,
+ * 1 first stage landed, 2 loop end, 3 partial stored, 4 stores acknowledged,
+ * 5 counted, 6 combined, 7 end, and inside a combine 8 live list built, 9 fence
+ * passed, 10 weights ready, 11 rows accumulated (the last key range of the
+ * workgroup wins; 0 = not reached).  Launches with more workgroups than the
+ * capacity record nothing.  The caller owns the buffer.
  */
-#define FD_TRACE_EVENTS 8
+#define FD_TRACE_EVENTS 12
 int fd_debug_set_trace(fd_handle_t h, void* device_buffer, int32_t capacity_workgroups);
 
 /* Text of the calling thread's last error ("" if none). Never NULL. */

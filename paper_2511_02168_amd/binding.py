@@ -144,7 +144,7 @@ def fd_debug_read_counters(h, n: int):
     return list(buf)
 
 
-FD_TRACE_EVENTS = 8
+FD_TRACE_EVENTS = 12
 
 
 def fd_debug_set_trace(h, buf, capacity_workgroups: int) -> None:

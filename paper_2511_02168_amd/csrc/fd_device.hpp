@@ -44,9 +44,9 @@ struct Params {
 };
 
 // ---- optional in-kernel timeline (for tuning; off unless a buffer is attached) --
-constexpr int kTraceEvents = 8;
+constexpr int kTraceEvents = 12;
 enum { kEvStart = 0, kEvFirstStage = 1, kEvLoopEnd = 2, kEvPartialOut = 3, kEvStoresAcked = 4, kEvCounted = 5,
-       kEvCombined = 6, kEvEnd = 7 };
+       kEvCombined = 6, kEvEnd = 7, kEvCombA = 8, kEvCombB = 9, kEvCombC = 10, kEvCombD = 11 };
 __device__ __forceinline__ void trace_event(const Params& p, int ev)
 {
     if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * kTraceEvents + ev] = wall_clock64();
@@ -230,18 +230,32 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
+// Maximum / sum over the 64 lanes: DPP inside each row of 16, then the 4 row results
+// are read from one lane each (no LDS traffic).  Every lane gets the result.
+__device__ __forceinline__ float row16_max(float x)
+{
+    x = fmaxf(x, dpp_f32<0xB1>(x));
+    x = fmaxf(x, dpp_f32<0x4E>(x));
+    x = fmaxf(x, dpp_f32<0x141>(x));
+    x = fmaxf(x, dpp_f32<0x140>(x));
+    return x;
+}
+
+__device__ __forceinline__ float lane_value(float x, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+
 __device__ __forceinline__ float wave_max(float x)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
+    x = row16_max(x);
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
 }
 
 __device__ __forceinline__ float wave_sum(float x)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-    return x;
+    x = row16_sum(x);
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
 
 // ---- end of an item: merge the workgroup's 4 wave states, normalise, store ------
@@ -294,127 +308,232 @@ __device__ inline void item_finish(const ItemSmem<ROWS>& sm, int G, float* dst_o
 // on which workgroup runs this.
 constexpr int kMaxSplits = 1024;
 
+constexpr int kCombineWCap = 4096;     // weights staged in LDS: heads x (live rows, padded)
+constexpr int kCombineGroup = 8;       // rows are loaded and padded in groups of this many
+
 struct CombineSmem {
-    int live[kMaxSplits];       // live slots, ascending
-    int n_live;
-    float M[16], invL[16];
+    // live slots in ascending order, row k at [(k % R) * stride + k / R] (R row slices, see below)
+    int live[kMaxSplits + 8 * 32];
+    int n_live, live0;
+    float w[kCombineWCap];      // exp2(lse - max) of row k of head g at [((g * R) + k % R) * KJ + k / R], 0 in the padding
+    float invL[16];             // per head
     float4 red[kWgThreads];     // cross-slice reduction
 };
 
-// HEADS_PER_WAVE >= ceil(G / 4); BATCH = rows whose loads a thread keeps in flight together.
-// Both only bound the registers this one-off code may claim inside a kernel.
-template <int HEADS_PER_WAVE, int BATCH>
+// Fallback of combine_tile for a tile whose weights do not fit the LDS staging area
+// (roughly more than kCombineWCap / G live partials): same formulas, every lse re-read
+// from memory.  Correct and slow; kept out of line of the fast path.
+__device__ inline void combine_tile_unstaged(const float* plse, const float* po, float* out_rows, float* lse_rows,
+                                                   int G, int n_live, const int* live, int log_r, int stride)
+{
+    const float4* po4 = reinterpret_cast<const float4*>(po);
+    const auto slot = [&](int k) { return live[(k & ((1 << log_r) - 1)) * stride + (k >> log_r)]; };
+    for (int pair = threadIdx.x; pair < G * (kD / 4); pair += kWgThreads) {
+        const int g = pair / (kD / 4), d4 = pair % (kD / 4);
+        float M = -INFINITY, L = 0.f;
+#pragma nounroll
+        for (int k = 0; k < n_live; ++k) M = fmaxf(M, plse[slot(k) * G + g]);
+#pragma nounroll
+        for (int k = 0; k < n_live; ++k) L += fast_exp2(plse[slot(k) * G + g] - M);
+        const float invL = __builtin_amdgcn_rcpf(L);
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma nounroll
+        for (int k = 0; k < n_live; ++k) {
+            const float w = fast_exp2(plse[slot(k) * G + g] - M);
+            const float4 x = po4[(size_t)(slot(k) * G + g) * (kD / 4) + d4];
+            o.x += w * x.x; o.y += w * x.y; o.z += w * x.z; o.w += w * x.w;
+        }
+        o.x *= invL; o.y *= invL; o.z *= invL; o.w *= invL;
+        reinterpret_cast<float4*>(out_rows)[pair] = o;
+        if (d4 == 0 && lse_rows) lse_rows[g] = (M + fast_log2(L)) * kLn2;
+    }
+}
+
+// Combine of one tile (Algorithm 4 Part 2; Equations of Section 4.2.1) by the workgroup
+// that saw the last arrival.  BATCH = rows whose loads a thread keeps in flight (a
+// multiple of kCombineGroup).
+//
+// This runs once per tile on the critical path of the call's tail, on ONE workgroup with
+// one wave per SIMD.  Two things cost time there: dependent memory round trips (0.4-1 us
+// each while the rest of the chip is still streaming) and instructions (a lone wave
+// retires only ~250 of them per microsecond).  Hence:
+//   1. wave 0 reads head 0's lse of every slot, up to 4 slots per lane in flight, and
+//      lists the live ones in ascending order (coherent loads: nothing is invalidated yet);
+//   2. acquire fence: from here on ordinary loads see the partials (they were written
+//      through to memory; the fence drops stale lines from this CU's L1 and this XCD's L2).
+//      Ordinary loads pull rows ~1.7x faster than coherent ones;
+//   3. one round trip: each thread requests its first BATCH rows of o; meanwhile 16 lanes
+//      per head fetch that head's lse values, reduce max and sum with DPP, and leave the
+//      rows' weights in LDS (zero in the padding, so the row loop needs no bounds logic);
+//   4. the row loop is a load, a 64-bit multiply-add for the address and four FMAs per row.
+// A thread owns 4 output dims of one head.  With fewer than 256 such pairs (G < 8), R
+// threads share a pair, thread slice s taking rows s, s+R, ...; the slices are summed
+// through LDS.  Rows are taken in ascending order within a slice and slices in ascending
+// order, so for a given partition the result does not depend on which workgroup runs this.
+template <int BATCH>
 __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm)
 {
+    static_assert(BATCH % kCombineGroup == 0 && BATCH <= 32, "row batch");
     const int G = p.G;          // <= 16
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
     const float* plse = p.part_lse + (size_t)tile * p.max_splits * G;
     const float* po = p.part_o + (size_t)tile * p.max_splits * G * kD;
+    float* out_rows = p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD;
+    float* lse_rows = p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr;
 
-    // phase A (one memory round trip): wave w takes heads w, w+4, ...; each lane loads
-    // the lse of slots lane, lane+64, ... for all of its wave's heads at once.  Empty
-    // slots hold -inf for every head, so they drop out of max and sum by themselves.
-    // Wave 0 also lists the live slots (ascending) from what it loaded for head 0.
-    constexpr int kPerLane = kMaxSplits / 64;
-    constexpr int kHeadsPerWave = HEADS_PER_WAVE;
-    {
-        float v[kHeadsPerWave][kPerLane];
+    // R = row slices = largest power of two with R * (pairs) <= 256
+    const int kPairs = G * (kD / 4);
+    const int log_r = G >= 5 ? 0 : G >= 3 ? 1 : G == 2 ? 2 : 3;
+    const int R = 1 << log_r;
+    const int stride = (kMaxSplits >> log_r) + 32;       // of one slice's live list
+
+    if (tid < 64) {
+        int count = 0, live0 = 0;
+#pragma nounroll
+        for (int base = 0; base < n; base += 256) {      // one trip up to 256 slots
+            float first[4];
 #pragma unroll
-        for (int j = 0; j < kHeadsPerWave; ++j) {
-            const int g = wave + kWaves * j;
+            for (int j = 0; j < 4; ++j) {
+                const int i = base + j * 64 + lane;
+                first[j] = -INFINITY;
+                if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * G]);
+            }
 #pragma unroll
-            for (int u = 0; u < kPerLane; ++u) {
-                const int i = lane + 64 * u;
-                v[j][u] = (g < G && i < n) ? load_agent(&plse[i * G + g]) : -INFINITY;
+            for (int j = 0; j < 4; ++j) {
+                if (base + j * 64 < n) {
+                    const bool live = first[j] != -INFINITY;
+                    const unsigned long long mask = __ballot(live);
+                    const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
+                    if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
+                    if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
+                    count += __popcll(mask);
+                }
             }
         }
-        if (wave == 0) {
-            int count = 0;
+        // padding up to the next multiple of R * kCombineGroup rows re-reads the first live row
+        for (int k = count + lane; k < count + R * (kCombineGroup + 1); k += 64)
+            sm.live[(k & (R - 1)) * stride + (k >> log_r)] = live0;
+        if (lane == 0) sm.n_live = count;
+    }
+    trace_event(p, kEvCombA);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();
+    const int n_live = sm.n_live;
+    trace_event(p, kEvCombB);
+    if (n_live == 0) {                                   // no key anywhere in the tile
+        for (int i = tid; i < G * kD; i += kWgThreads) out_rows[i] = 0.f;
+        if (tid < G && lse_rows) lse_rows[tid] = -INFINITY;
+        __syncthreads();
+        return;
+    }
+    // rows per slice, padded to whole groups
+    const int KJ = (((n_live + R - 1) >> log_r) + kCombineGroup - 1) & ~(kCombineGroup - 1);
+    if (G * R * KJ > kCombineWCap) {
+        combine_tile_unstaged(plse, po, out_rows, lse_rows, G, n_live, sm.live, log_r, stride);
+        __syncthreads();
+        return;
+    }
+
+    // thread -> (pair, slice) without an integer division
+    const int slice = (int)(((tid >> 5) + 0.5f) * __builtin_amdgcn_rcpf((float)G));
+    const int pair0 = tid - slice * kPairs;
+    const size_t row_f4 = (size_t)G * (kD / 4);          // float4 per slot
+    const float4* po4 = reinterpret_cast<const float4*>(po);
+    const int* my_live = &sm.live[slice * stride];
+
+    float4 x[BATCH];
+    const auto load_rows = [&](int j0, int pair) {       // groups of rows [j0, j0 + BATCH) below KJ
 #pragma unroll
-            for (int u = 0; u < kPerLane; ++u) {
-                const bool live = v[0][u] != -INFINITY;
-                const unsigned long long mask = __ballot(live);
-                if (live) sm.live[count + __popcll(mask & ((1ull << lane) - 1ull))] = lane + 64 * u;
-                count += __popcll(mask);
+        for (int grp = 0; grp < BATCH / kCombineGroup; ++grp) {
+            if (j0 + grp * kCombineGroup < KJ) {
+#pragma unroll
+                for (int u = 0; u < kCombineGroup; ++u) {
+                    const int j = grp * kCombineGroup + u;
+                    x[j] = po4[my_live[j0 + j] * row_f4 + pair];
+                }
             }
-            if (lane == 0) sm.n_live = count;
         }
-#pragma unroll
-        for (int j = 0; j < kHeadsPerWave; ++j) {
-            const int g = wave + kWaves * j;
-            if (g >= G) break;
-            float mx = v[j][0];
-#pragma unroll
-            for (int u = 1; u < kPerLane; ++u) mx = fmaxf(mx, v[j][u]);
-            mx = wave_max(mx);
-            float sum = 0.f;
-            if (mx != -INFINITY) {
-#pragma unroll
-                for (int u = 0; u < kPerLane; ++u) sum += fast_exp2(v[j][u] - mx);
-            }
-            sum = wave_sum(sum);
-            if (lane == 0) {
-                sm.M[g] = mx;
-                sm.invL[g] = sum > 0.f ? 1.0f / sum : 0.f;
-                if (p.lse) p.lse[(size_t)b * p.Hq + kvh * G + g] = sum > 0.f ? (mx + fast_log2(sum)) * kLn2 : -INFINITY;
-            }
+    };
+    const bool active0 = slice < R && pair0 < kPairs;
+    if (active0) load_rows(0, pair0);
+
+    // weights: 16 lanes per head, lane j takes rows j, j+16, ...
+    if ((tid >> 4) < G) {
+        const int g = tid >> 4, j = tid & 15;
+        float* wg = &sm.w[g * R * KJ];
+        const auto at = [&](int k) { return (k & (R - 1)) * KJ + (k >> log_r); };
+        float m = -INFINITY;
+#pragma nounroll
+        for (int k = j; k < n_live; k += 16) {
+            const float v = plse[sm.live[(k & (R - 1)) * stride + (k >> log_r)] * G + g];
+            wg[at(k)] = v;
+            m = fmaxf(m, v);
+        }
+        const float M = row16_max(m);
+        float l = 0.f;
+#pragma nounroll
+        for (int k = j; k < R * KJ; k += 16) {
+            const float e = k < n_live ? fast_exp2(wg[at(k)] - M) : 0.f;
+            wg[at(k)] = e;
+            l += e;
+        }
+        const float L = row16_sum(l);
+        if (j == 0) {
+            sm.invL[g] = __builtin_amdgcn_rcpf(L);
+            if (lse_rows) lse_rows[g] = (M + fast_log2(L)) * kLn2;
         }
     }
     __syncthreads();
-    const int n_live = sm.n_live;
+    trace_event(p, kEvCombC);
 
-    // phase B: out[g][d] = sum_k w_k[g] * o_k[g][d].  A thread owns one (g, 4 dims)
-    // pair; when there are fewer pairs than threads, R threads share a pair, each
-    // taking every R-th live row, and their sums are added in slice order.  The
-    // loads of 16 rows are in flight together (one round trip per 16 rows).
-    const int kPairs = G * (kD / 4);
-    const int R = kPairs >= kWgThreads ? 1 : kWgThreads / kPairs;
-    constexpr int kBatch = BATCH;
-    float4* dst = reinterpret_cast<float4*>(p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD);
+#pragma nounroll
     for (int pbase = 0; pbase < kPairs; pbase += kWgThreads) {
-        const int pair = pbase + (R > 1 ? tid % kPairs : tid);
-        const int slice = R > 1 ? tid / kPairs : 0;
-        const bool active = pair < kPairs && slice < R;
+        const int pair = pbase + pair0;
+        const bool active = slice < R && pair < kPairs;
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
         if (active) {
-            const int g = pair / (kD / 4), d4 = pair % (kD / 4);
-            const float M = sm.M[g], invL = sm.invL[g];
-            for (int k0 = slice; k0 < n_live; k0 += R * kBatch) {
-                float lw[kBatch];
-                float2 x01[kBatch], x23[kBatch];
+            const int g = pair >> 5;
+            const float* my_w = &sm.w[(g * R + slice) * KJ];
+            if (pbase > 0) load_rows(0, pair);
+            int j0 = 0;
+#pragma nounroll
+            while (true) {
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const int k = k0 + R * u;
-                    const int i = sm.live[k < n_live ? k : k0];
-                    const float* src = po + ((size_t)(i * G + g) * (kD / 4) + d4) * 4;
-                    lw[u] = load_agent(&plse[i * G + g]);
-                    x01[u] = load_agent2(src);
-                    x23[u] = load_agent2(src + 2);
-                }
+                for (int grp = 0; grp < BATCH / kCombineGroup; ++grp) {
+                    if (j0 + grp * kCombineGroup < KJ) {
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const float w = (k0 + R * u) < n_live ? fast_exp2(lw[u] - M) * invL : 0.f;
-                    o.x += w * x01[u].x;
-                    o.y += w * x01[u].y;
-                    o.z += w * x23[u].x;
-                    o.w += w * x23[u].y;
+                        for (int u = 0; u < kCombineGroup; ++u) {
+                            const int j = grp * kCombineGroup + u;
+                            const float w = my_w[j0 + j];
+                            o.x += w * x[j].x;
+                            o.y += w * x[j].y;
+                            o.z += w * x[j].z;
+                            o.w += w * x[j].w;
+                        }
+                    }
                 }
+                j0 += BATCH;
+                if (j0 >= KJ) break;
+                load_rows(j0, pair);
             }
+            const float invL = sm.invL[g];
+            o.x *= invL; o.y *= invL; o.z *= invL; o.w *= invL;
         }
+        trace_event(p, kEvCombD);
         if (R > 1) {
             sm.red[tid] = o;
             __syncthreads();
             if (active && slice == 0) {
+#pragma nounroll
                 for (int r = 1; r < R; ++r) {
                     const float4 t = sm.red[r * kPairs + pair];
                     o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
                 }
-                dst[pair] = o;
+                reinterpret_cast<float4*>(out_rows)[pair] = o;
             }
-            __syncthreads();
         } else if (active) {
-            dst[pair] = o;
+            reinterpret_cast<float4*>(out_rows)[pair] = o;
         }
     }
     __syncthreads();

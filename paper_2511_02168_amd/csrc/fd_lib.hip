@@ -55,7 +55,7 @@ struct SchedSmem {
 // workgroup that completes a tile's split count merges the tile: paper Section
 // 4.2.5 / Algorithm 4 without the barrier and without the second launch).
 // !FUSED: steps a1-a6 only (kernel 1 of the bulk-synchronous baseline, Section 4.2.2).
-template <bool FUSED, int COMB_HEADS, int COMB_BATCH, class Path>
+template <bool FUSED, int COMB_BATCH, class Path>
 __device__ __forceinline__ void persistent_loop(const Params& p, const Path& path, SchedSmem& ss, CombineSmem& comb)
 {
     const int G = p.G;
@@ -123,7 +123,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             __syncthreads();
             trace_event(p, kEvCounted);
             if (ss.is_last) {
-                combine_tile<COMB_HEADS, COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb);
+                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb);
                 if (threadIdx.x == 0)                               // re-arm for the next call
                     __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 trace_event(p, kEvCombined);
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(kWgThreads, (G <= 5 ? 2 : 1)) void fd_valu_kernel(P
 {
     __shared__ ValuWgSmem<G> sm;
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, (G + 3) / 4, 8>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
+    persistent_loop<FUSED, 16>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
 }
 
 extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 {
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, 4, 16>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+    persistent_loop<FUSED, (NST >= 4 ? 32 : 16)>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
 // Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
@@ -173,7 +173,9 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
     }
     __syncthreads();
     if (done) return;
-    combine_tile<4, 16>(p, tile, b, kvh, n, sm);
+    trace_event(p, kEvStart);
+    combine_tile<32>(p, tile, b, kvh, n, sm);
+    trace_event(p, kEvEnd);
 }
 
 }  // namespace fd

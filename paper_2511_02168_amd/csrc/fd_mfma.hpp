@@ -211,10 +211,8 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     const float sl2 = p.scale_log2;
     constexpr int P = NST - 1;                            // stages in flight ahead of the one being consumed
 
-    for (int s = 0; s < P && s < mine; ++s)
-        mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kbase, vbase, j0 + (wave + kWaves * s) * kMfBlockKeys, j1,
-                         lane);
-    // a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero
+    // a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero.
+    // Requested first: the round trip overlaps the issue of the first stages.
     bf16x8_t qb[4];
     {
         const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * G + head) * kRowU4;
@@ -224,12 +222,14 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             if (head < G) v = qp[4 * t + kg];
             qb[t] = __builtin_bit_cast(bf16x8_t, v);
         }
-        // Requested after the first stages so that both arrive in one memory round trip.
-        // Make the compiler wait for these loads HERE: the loop below must contain no
-        // compiler-generated vmcnt wait, which would also drain the stage loads the loop
-        // keeps in flight (they are issued from inline asm, invisible to its counter).
-        asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
     }
+    for (int s = 0; s < P && s < mine; ++s)
+        mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kbase, vbase, j0 + (wave + kWaves * s) * kMfBlockKeys, j1,
+                         lane);
+    // Make the compiler wait for the q loads HERE: the loop below must contain no
+    // compiler-generated vmcnt wait, which would also drain the stage loads the loop
+    // keeps in flight (they are issued from inline asm, invisible to its counter).
+    asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
     for (int s = 0; s < mine; ++s) {
         if (s + P < mine)
             mfma_issue_stage(my_ring_lds + ((s + P) % NST) * kMfStageBytes, kbase, vbase,

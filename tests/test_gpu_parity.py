@@ -206,6 +206,27 @@ def test_edge_sequence_lengths_group8(S):
         full_parity(wl, inp, n, max_splits=8, what=f"G=8 S={S} n={n}")
 
 
+@pytest.mark.parametrize("G,n_splits,per_cu", [(1, 512, 2), (2, 300, 2), (4, 256, 1), (8, 256, 1), (8, 1000, 2),
+                                               (16, 248, 1), (16, 512, 2), (16, 1024, 2)])
+def test_one_tile_with_many_live_partials(G, n_splits, per_cu):
+    """A single (batch, KV head) tile cut into more splits than there are workgroups: every
+    workgroup leaves one partial, so the combine sees hundreds of live rows (several row
+    batches per thread, a liveness scan of more than 256 slots, and for G = 16 with more
+    than 248 rows the variant that does not stage its weights in LDS)."""
+    S = 64 * n_splits + 37
+    wl = _generic(1, G, 1, S, 900 + G + n_splits)
+    say(f"case one tile, G={G}, n_splits={n_splits}, wgs_per_cu={per_cu}, S={S}")
+    inp = fi.make_inputs(wl, "cuda")
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    with fd.FlashDecode(1, G, 1, S, max_splits=1024) as dec:
+        fd.fd_set_option(dec.h, fd.FD_OPT_WGS_PER_CU, per_cu)
+        fd.fd_debug_poison_workspace(dec.h)
+        out, lse = run_both(dec, inp, n_splits)
+        say(f"  grid {fd.fd_get_option(dec.h, fd.FD_INFO_LAST_GRID)} workgroups")
+    check_out(out, ref_o, f"many partials G={G} n={n_splits}")
+    check_lse(lse, ref_l, f"many partials G={G} n={n_splits}")
+
+
 def test_more_splits_than_key_blocks():
     wl = _generic(2, 4, 1, 100, 300)
     say("case n_splits=16 over 100 keys (most splits empty)")
