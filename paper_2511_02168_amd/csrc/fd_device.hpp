@@ -201,6 +201,12 @@ __device__ __forceinline__ void store_agent(float* p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// 16 bytes (16-byte aligned) in one coherent store
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_agent4(float* p, f32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
 __device__ __forceinline__ float load_agent(const float* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -263,37 +269,45 @@ __device__ __forceinline__ float wave_sum(float x)
 // ROWS query heads of the tile here; all in base-2 units.
 template <int ROWS>
 struct ItemSmem {
-    float m[kWaves][ROWS];
-    float l[kWaves][ROWS];
+    float m[ROWS][kWaves];
+    float l[ROWS][kWaves];
     float acc[kWaves][ROWS][kD];
 };
 
 // a6: o = sum_w acc_w 2^(m_w - M) / sum_w l_w 2^(m_w - M), lse = M + log2(sum).
 // SHARED: the destination is a partial another workgroup may read in this launch
 // (coherent stores).  Call with the wave states written and a barrier passed;
-// returns with every thread past its last read of sm.
+// returns with every thread past its last read of sm.  A thread produces 4 dims of
+// one head: this tail runs with one wave per SIMD, where every instruction counts.
 template <int ROWS, bool SHARED>
 __device__ inline void item_finish(const ItemSmem<ROWS>& sm, int G, float* dst_o, float* dst_lse, float lse_mul)
 {
-    for (int idx = threadIdx.x; idx < G * kD; idx += kWgThreads) {
-        const int g = idx / kD, d = idx % kD;
-        float M = sm.m[0][g];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm.m[w][g]);
-        float L = 0.f, o = 0.f;
+    static_assert(kWaves == 4, "the wave states of a head are read as one float4");
+#pragma nounroll
+    for (int idx = threadIdx.x; idx < G * (kD / 4); idx += kWgThreads) {
+        const int g = idx >> 5, d4 = idx & 31;
+        const float4 mv = *reinterpret_cast<const float4*>(sm.m[g]);
+        const float4 lv = *reinterpret_cast<const float4*>(sm.l[g]);
+        const float M = fmaxf(fmaxf(mv.x, mv.y), fmaxf(mv.z, mv.w));
+        const float f[4] = {fast_exp2(mv.x - M), fast_exp2(mv.y - M), fast_exp2(mv.z - M), fast_exp2(mv.w - M)};
+        const float L = (lv.x * f[0] + lv.y * f[1]) + (lv.z * f[2] + lv.w * f[3]);
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float f = fast_exp2(sm.m[w][g] - M);
-            L += sm.l[w][g] * f;
-            o += sm.acc[w][g][d] * f;
+            const float4 a = *reinterpret_cast<const float4*>(&sm.acc[w][g][4 * d4]);
+            o[0] += a.x * f[w];
+            o[1] += a.y * f[w];
+            o[2] += a.z * f[w];
+            o[3] += a.w * f[w];
         }
-        const float res = o / L, res_lse = (M + fast_log2(L)) * lse_mul;
+        o *= __builtin_amdgcn_rcpf(L);
+        const float res_lse = (M + fast_log2(L)) * lse_mul;
         if (SHARED) {
-            store_agent(&dst_o[idx], res);
-            if (d == 0) store_agent(&dst_lse[g], res_lse);
+            store_agent4(&dst_o[4 * idx], o);
+            if (d4 == 0) store_agent(&dst_lse[g], res_lse);
         } else {
-            dst_o[idx] = res;
-            if (d == 0 && dst_lse) dst_lse[g] = res_lse;
+            *reinterpret_cast<f32x4*>(&dst_o[4 * idx]) = o;
+            if (d4 == 0 && dst_lse) dst_lse[g] = res_lse;
         }
     }
     __syncthreads();
@@ -442,6 +456,19 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     const float4* po4 = reinterpret_cast<const float4*>(po);
     const int* my_live = &sm.live[slice * stride];
 
+    // weights: 16 lanes per head, lane j takes rows j, j+16, ...  The lse loads of the first
+    // 64 rows go out BEFORE the row loads, so that the weights do not wait for the rows.
+    const bool stat_lane = (tid >> 4) < G;
+    const int sg = tid >> 4, sj = tid & 15;
+    const auto live_at = [&](int k) { return sm.live[(k & (R - 1)) * stride + (k >> log_r)]; };
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = sj + 16 * i;
+        v[i] = -INFINITY;
+        if (stat_lane && k < n_live) v[i] = plse[live_at(k) * G + sg];
+    }
+
     float4 x[BATCH];
     const auto load_rows = [&](int j0, int pair) {       // groups of rows [j0, j0 + BATCH) below KJ
 #pragma unroll
@@ -458,30 +485,37 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     const bool active0 = slice < R && pair0 < kPairs;
     if (active0) load_rows(0, pair0);
 
-    // weights: 16 lanes per head, lane j takes rows j, j+16, ...
-    if ((tid >> 4) < G) {
-        const int g = tid >> 4, j = tid & 15;
-        float* wg = &sm.w[g * R * KJ];
+    if (stat_lane) {
+        float* wg = &sm.w[sg * R * KJ];
         const auto at = [&](int k) { return (k & (R - 1)) * KJ + (k >> log_r); };
-        float m = -INFINITY;
+        float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
 #pragma nounroll
-        for (int k = j; k < n_live; k += 16) {
-            const float v = plse[sm.live[(k & (R - 1)) * stride + (k >> log_r)] * G + g];
-            wg[at(k)] = v;
-            m = fmaxf(m, v);
+        for (int k = sj + 64; k < n_live; k += 16) {     // rows past the first 64: rare, fetched here
+            const float t = plse[live_at(k) * G + sg];
+            wg[at(k)] = t;
+            m = fmaxf(m, t);
         }
         const float M = row16_max(m);
         float l = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = sj + 16 * i;
+            if (k < R * KJ) {
+                const float e = fast_exp2(v[i] - M);     // 0 for the padding (v = -inf)
+                wg[at(k)] = e;
+                l += e;
+            }
+        }
 #pragma nounroll
-        for (int k = j; k < R * KJ; k += 16) {
+        for (int k = sj + 64; k < R * KJ; k += 16) {
             const float e = k < n_live ? fast_exp2(wg[at(k)] - M) : 0.f;
             wg[at(k)] = e;
             l += e;
         }
         const float L = row16_sum(l);
-        if (j == 0) {
-            sm.invL[g] = __builtin_amdgcn_rcpf(L);
-            if (lse_rows) lse_rows[g] = (M + fast_log2(L)) * kLn2;
+        if (sj == 0) {
+            sm.invL[sg] = __builtin_amdgcn_rcpf(L);
+            if (lse_rows) lse_rows[sg] = (M + fast_log2(L)) * kLn2;
         }
     }
     __syncthreads();

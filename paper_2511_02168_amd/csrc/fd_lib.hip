@@ -141,11 +141,11 @@ union __attribute__((aligned(16))) ValuWgSmem {
 };
 
 template <int G, bool FUSED>
-__global__ __launch_bounds__(kWgThreads, (G <= 5 ? 2 : 1)) void fd_valu_kernel(Params p)
+__global__ __launch_bounds__(kWgThreads, (G <= 3 ? 2 : 1)) void fd_valu_kernel(Params p)
 {
     __shared__ ValuWgSmem<G> sm;
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, 16>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
+    persistent_loop<FUSED, (G <= 2 ? 16 : 8)>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
 }
 
 extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 {
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, (NST >= 4 ? 32 : 16)>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+    persistent_loop<FUSED, (NST >= 4 ? 32 : 8)>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
 // Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
@@ -336,7 +336,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     // The MFMA kernel trades ring depth for residency: 1 workgroup per CU with 4 stages
     // per wave, or 2 per CU with 2 stages.
     const long long items_max = (long long)tiles * (n_splits > 0 ? n_splits : c.max_splits);
-    int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : (path == 2 ? 1 : 2);
+    int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : ((path == 2 || G >= 4) ? 1 : 2);
     if (path == 2 && per_cu > 2) per_cu = 2;
     long long grid = (long long)h->num_cus * per_cu;
     if (grid > items_max) grid = items_max;

@@ -250,8 +250,8 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     ItemSmem<kMfRows>& sm = *reinterpret_cast<ItemSmem<kMfRows>*>(ring);
     if (head < G) {
         if (kg == 0) {
-            sm.m[wave][head] = st.m;
-            sm.l[wave][head] = st.l;
+            sm.m[head][wave] = st.m;
+            sm.l[head][wave] = st.l;
         }
 #pragma unroll
         for (int db = 0; db < 8; ++db)

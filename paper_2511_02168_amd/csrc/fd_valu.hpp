@@ -220,8 +220,8 @@ __device__ inline void valu_item(const Params& p, int b, int kvh, int j0, int j1
             d[0] = make_float4(st.acc[g][0], st.acc[g][1], st.acc[g][2], st.acc[g][3]);
             d[1] = make_float4(st.acc[g][4], st.acc[g][5], st.acc[g][6], st.acc[g][7]);
             if (c == 0) {
-                sm.m[wave][g] = st.m[g];
-                sm.l[wave][g] = st.l[g];
+                sm.m[g][wave] = st.m[g];
+                sm.l[g][wave] = st.l[g];
             }
         }
     }
