@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
+    ap.add_argument("--ring-stages", type=int, default=0)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (known HBM traffic: 1 GiB read + 1 GiB "
                          "written per launch) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -125,7 +126,7 @@ def main():
     max_splits = wl.n_splits if wl.n_splits > 0 else -(-wl.S_max // 512)
     dec = fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max_splits)
     for key, val in ((fd.FD_OPT_XCD_GROUPS, args.xcd_groups), (fd.FD_OPT_WGS_PER_CU, args.wgs_per_cu),
-                     (fd.FD_OPT_PATH, args.path)):
+                     (fd.FD_OPT_PATH, args.path), (fd.FD_OPT_RING_STAGES, args.ring_stages)):
         if val:
             fd.fd_set_option(dec.h, key, val)
     out = torch.empty(wl.B, wl.Hq, wl.D, device="cuda", dtype=torch.float32)

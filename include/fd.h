@@ -131,15 +131,20 @@ int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void*
  * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.
  *   FD_OPT_PATH          0 auto (MFMA kernel when Hq/Hkv >= 4, VALU kernel below),
  *                        1 force VALU (Hq/Hkv <= 8 only), 2 force MFMA
- *   FD_OPT_XCD_GROUPS    0 auto, 1 = one global item list, 8 = items of a tile
- *                        stay on one XCD (tile t -> workgroups with id % 8 == t % 8)
+ *   FD_OPT_XCD_GROUPS    0 auto (8 when B*Hkv is a multiple of 8, except for at most 32
+ *                        tiles with S_max > 16384; else 1), 1 = one global item list,
+ *                        8 = items of a tile stay on one XCD (tile t -> workgroups with
+ *                        id % 8 == t % 8)
  *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto)
+ *   FD_OPT_RING_STAGES   MFMA kernel: stages (16 keys of K and V, 8 KB) in each wave's
+ *                        LDS ring: 0 auto (2), 2, 3 or 4; with 2 workgroups per CU always 2
  *   FD_INFO_*            read-only, through fd_get_option
  */
 enum {
     FD_OPT_PATH = 1,
     FD_OPT_XCD_GROUPS = 2,
     FD_OPT_WGS_PER_CU = 3,
+    FD_OPT_RING_STAGES = 4,
     FD_INFO_NUM_CUS = 100,
     FD_INFO_LAST_GRID = 101,   /* workgroups of the last fused / split launch */
     FD_INFO_LAST_PATH = 102    /* 1 VALU, 2 MFMA */

@@ -150,12 +150,14 @@ __global__ __launch_bounds__(kWgThreads, (G <= 3 ? 2 : 1)) void fd_valu_kernel(P
 
 extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
 
-template <int NST, bool FUSED>
+// CB = rows a combining thread keeps in flight: 32 when the workgroup has the CU to itself
+// (512 registers per lane), 8 when two workgroups share it.
+template <int NST, bool FUSED, int CB>
 __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 {
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, (NST >= 4 ? 32 : 8)>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+    persistent_loop<FUSED, CB>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
 // Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
@@ -219,7 +221,7 @@ struct fd_handle_s {
     int num_cus;
     void* workspace;
     Layout lay;
-    int opt_path, opt_xcd, opt_wgs_per_cu;
+    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring;
     int last_grid, last_path;
     unsigned long long* trace;
     int trace_capacity;      // workgroups the trace buffer has room for
@@ -283,7 +285,7 @@ int launch_valu(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
-template <int NST>
+template <int NST, int CB>
 int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
 {
     // more than 64 KB of dynamic LDS has to be granted once per kernel and device
@@ -293,19 +295,19 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     const size_t ring = (size_t)fd::mfma_ring_bytes(NST);
     if (granted_device[fused] != dev) {
         if (fused)
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true>,
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true, CB>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
         else
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false>,
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false, CB>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
         granted_device[fused] = dev;
     }
     if (fused) {
-        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true, CB>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
         FD_HIP(hipGetLastError());
         return FD_OK;
     }
-    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false, CB>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
     FD_HIP(hipGetLastError());
     return launch_combine(p, st);
 }
@@ -333,15 +335,21 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     if (path == 1 && G > 8) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for Hq/Hkv <= 8 (got %d)", G);
 
     // persistent grid: a fixed number of workgroups per CU, never more than there are items.
-    // The MFMA kernel trades ring depth for residency: 1 workgroup per CU with 4 stages
-    // per wave, or 2 per CU with 2 stages.
+    // MFMA kernel: one workgroup per CU and a ring of 2 stages per wave (ONE 8 KB stage in
+    // flight per wave, 8 MB on the whole chip) measured fastest: deeper rings only lengthen
+    // the queues in front of memory, which every dependent access of the tail then waits in.
     const long long items_max = (long long)tiles * (n_splits > 0 ? n_splits : c.max_splits);
     int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : ((path == 2 || G >= 4) ? 1 : 2);
     if (path == 2 && per_cu > 2) per_cu = 2;
     long long grid = (long long)h->num_cus * per_cu;
     if (grid > items_max) grid = items_max;
     int X = h->opt_xcd;
-    if (X == 0) X = (tiles % 8 == 0) ? 8 : 1;
+    // Work lists: one per XCD (the workgroups that exchange a tile's partials share an L2 and
+    // finish together, which keeps the tail short) or one for the chip (every XCD streams
+    // from all over the cache).  Measured: with few, large tiles (at most 32 tiles of more
+    // than 16K keys) the single list streams 2-10 % faster; everywhere else the lists per
+    // XCD are as fast or faster (up to 6 % on short calls).
+    if (X == 0) X = (tiles % 8 == 0 && !(tiles <= 32 && c.S_max > 16384)) ? 8 : 1;
     if (grid < 8) X = 1;
     if (X == 8) grid -= grid % 8;
     if (n_splits == 0 && (tiles + X - 1) / X > fd::kMaxGroupTiles)
@@ -369,7 +377,14 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     hipStream_t st = (hipStream_t)stream;
     h->last_grid = (int)grid;
     h->last_path = path;
-    if (path == 2) return per_cu == 1 ? launch_mfma<4>(p, fused, (int)grid, st) : launch_mfma<2>(p, fused, (int)grid, st);
+    if (path == 2) {
+        int nst = h->opt_ring > 0 ? h->opt_ring : 2;
+        if (per_cu > 1) nst = 2;                       // two workgroups per CU share the LDS
+        if (per_cu > 1) return launch_mfma<2, 8>(p, fused, (int)grid, st);
+        if (nst == 4) return launch_mfma<4, 32>(p, fused, (int)grid, st);
+        if (nst == 3) return launch_mfma<3, 32>(p, fused, (int)grid, st);
+        return launch_mfma<2, 32>(p, fused, (int)grid, st);
+    }
     switch (G) {
         case 1: return launch_valu<1>(p, fused, (int)grid, st);
         case 2: return launch_valu<2>(p, fused, (int)grid, st);
@@ -413,7 +428,7 @@ int fd_create(const fd_config* cfg, fd_handle_t* out)
     h->device = dev;
     h->num_cus = prop.multiProcessorCount;
     h->lay = make_layout(*cfg);
-    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = 0;
+    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = 0;
     h->last_grid = h->last_path = 0;
     h->trace = nullptr;
     h->trace_capacity = 0;
@@ -483,6 +498,10 @@ int fd_set_option(fd_handle_t h, int32_t key, int32_t value)
             if (value < 0 || value > 16) return fail(FD_ERR_INVALID_ARG, "FD_OPT_WGS_PER_CU must be in 0..16");
             h->opt_wgs_per_cu = value;
             return FD_OK;
+        case FD_OPT_RING_STAGES:
+            if (value != 0 && (value < 2 || value > 4)) return fail(FD_ERR_INVALID_ARG, "FD_OPT_RING_STAGES must be 0, 2, 3 or 4");
+            h->opt_ring = value;
+            return FD_OK;
         default:
             return fail(FD_ERR_INVALID_ARG, "unknown or read-only option %d", key);
     }
@@ -497,6 +516,7 @@ int fd_get_option(fd_handle_t h, int32_t key, int32_t* value)
         case FD_OPT_PATH: *value = h->opt_path; return FD_OK;
         case FD_OPT_XCD_GROUPS: *value = h->opt_xcd; return FD_OK;
         case FD_OPT_WGS_PER_CU: *value = h->opt_wgs_per_cu; return FD_OK;
+        case FD_OPT_RING_STAGES: *value = h->opt_ring; return FD_OK;
         case FD_INFO_NUM_CUS: *value = h->num_cus; return FD_OK;
         case FD_INFO_LAST_GRID: *value = h->last_grid; return FD_OK;
         case FD_INFO_LAST_PATH: *value = h->last_path; return FD_OK;

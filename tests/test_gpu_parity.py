@@ -197,6 +197,29 @@ def test_both_kernels_on_the_same_shapes(G, path, per_cu):
             check_lse(lse, ref_l, f"path={path} G={G} n={n}")
 
 
+@pytest.mark.parametrize("stages", [2, 3, 4])
+def test_every_ring_depth_of_the_mfma_kernel(stages):
+    """FD_OPT_RING_STAGES: the depth of each wave's LDS ring changes how far the K/V stream
+    runs ahead, never the arithmetic: all depths give bitwise the same result."""
+    wl = _generic(3, 16, 2, 2100, 260 + stages, ragged=True)
+    say(f"case ring stages={stages}, G=8, ragged S<=2100")
+    inp = fi.make_inputs(wl, "cuda")
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    outs = []
+    for st in (stages, 0):
+        with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=8) as dec:
+            fd.fd_set_option(dec.h, fd.FD_OPT_RING_STAGES, st)
+            assert fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES) == st
+            for n in (1, 5, 0):
+                fd.fd_debug_poison_workspace(dec.h)
+                out, lse = run_both(dec, inp, n)
+                check_out(out, ref_o, f"stages={st} n={n}")
+                check_lse(lse, ref_l, f"stages={st} n={n}")
+                outs.append(out)
+    for a, b in zip(outs[:3], outs[3:]):
+        assert np.array_equal(a, b), "ring depth changed the result"
+
+
 @pytest.mark.parametrize("S", [1, 15, 16, 17, 63, 64, 65, 100, 1023, 1025])
 def test_edge_sequence_lengths_group8(S):
     wl = _generic(2, 16, 2, S, 150 + S)
@@ -335,4 +358,9 @@ def test_argument_errors_on_device():
         with pytest.raises(fd.FdError) as e:
             fd.fd_decode(dec.h, t, kv, kv, sl, out, None, -1)
         assert e.value.code == fd.FD_ERR_INVALID_ARG
+        for key, bad in ((fd.FD_OPT_PATH, 3), (fd.FD_OPT_XCD_GROUPS, 4), (fd.FD_OPT_WGS_PER_CU, 17),
+                         (fd.FD_OPT_RING_STAGES, 5), (fd.FD_OPT_RING_STAGES, 1), (999, 0), (fd.FD_INFO_NUM_CUS, 1)):
+            with pytest.raises(fd.FdError) as e:
+                fd.fd_set_option(dec.h, key, bad)
+            assert e.value.code == fd.FD_ERR_INVALID_ARG
         assert fd.fd_get_option(dec.h, fd.FD_INFO_NUM_CUS) == 256
