@@ -384,12 +384,26 @@ __device__ inline void combine_tile_unstaged(const float* plse, const float* po,
 // threads share a pair, thread slice s taking rows s, s+R, ...; the slices are summed
 // through LDS.  Rows are taken in ascending order within a slice and slices in ascending
 // order, so for a given partition the result does not depend on which workgroup runs this.
+// What the combining workgroup of the fused kernel knows about who wrote the tile's
+// partials: the tile's items are [t0, t0 + n) of a work list of n_items items cut into
+// `members` contiguous blocks (see WorkList); block w wrote one partial, into the slot of
+// its first item of this tile, if it holds any of the tile's items and that item's key
+// range is not empty.
+struct TileSchedule {
+    int t0, n_items, members, split_keys, S;
+};
+
 template <int BATCH>
-__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm)
+__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm,
+                                    const TileSchedule* sch = nullptr)
 {
     static_assert(BATCH % kCombineGroup == 0 && BATCH <= 32, "row batch");
     const int G = p.G;          // <= 16
-    const int tid = threadIdx.x;
+    // Opaque to the optimiser: everything below that depends on the thread index is then
+    // computed here, not hoisted out of the caller's loop into registers that would stay
+    // occupied during the K/V streaming.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63;
     const float* plse = p.part_lse + (size_t)tile * p.max_splits * G;
     const float* po = p.part_o + (size_t)tile * p.max_splits * G * kD;
@@ -404,24 +418,44 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
 
     if (tid < 64) {
         int count = 0, live0 = 0;
+        if (sch) {
+            // the live slots follow from the schedule: no memory access
+            const long long E = sch->n_items, M = sch->members;
+            const int t0 = sch->t0;
+            const int w_first = max(0, (int)(t0 * M / E) - 1);
+            const int w_end = min((int)M, (int)(((long long)(t0 + n) * M + E - 1) / E) + 1);
 #pragma nounroll
-        for (int base = 0; base < n; base += 256) {      // one trip up to 256 slots
-            float first[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = base + j * 64 + lane;
-                first[j] = -INFINITY;
-                if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * G]);
+            for (int base = w_first; base < w_end; base += 64) {
+                const int w = base + lane;
+                const int lo = max((int)(w * E / M), t0), hi = min((int)((w + 1) * E / M), t0 + n);
+                const bool live = w < w_end && lo < hi && (long long)(lo - t0) * sch->split_keys < sch->S;
+                const unsigned long long mask = __ballot(live);
+                const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
+                if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = lo - t0;
+                if (count == 0 && mask != 0)
+                    live0 = __builtin_amdgcn_readlane(lo - t0, __builtin_ctzll(mask));
+                count += __popcll(mask);
             }
+        } else {
+#pragma nounroll
+            for (int base = 0; base < n; base += 256) {      // one trip up to 256 slots
+                float first[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (base + j * 64 < n) {
-                    const bool live = first[j] != -INFINITY;
-                    const unsigned long long mask = __ballot(live);
-                    const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
-                    if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
-                    if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
-                    count += __popcll(mask);
+                for (int j = 0; j < 4; ++j) {
+                    const int i = base + j * 64 + lane;
+                    first[j] = -INFINITY;
+                    if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * G]);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (base + j * 64 < n) {
+                        const bool live = first[j] != -INFINITY;
+                        const unsigned long long mask = __ballot(live);
+                        const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
+                        if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
+                        if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
+                        count += __popcll(mask);
+                    }
                 }
             }
         }

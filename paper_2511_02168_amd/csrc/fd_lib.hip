@@ -75,6 +75,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
         it.S = __builtin_amdgcn_readfirstlane(it.S);
         const int s1 = min(it.n, it.split + (wl.last - e));
         const int run = s1 - it.split;
+        const int t0 = e - it.split;         // the tile's first item in this work list
         e += run;
         const int c = split_keys_of(it.S, it.n);
         const int j0 = min(it.split * c, it.S);
@@ -123,7 +124,8 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             __syncthreads();
             trace_event(p, kEvCounted);
             if (ss.is_last) {
-                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb);
+                const TileSchedule sch = {t0, wl.n_items, wl.members, c, it.S};
+                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, &sch);
                 if (threadIdx.x == 0)                               // re-arm for the next call
                     __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 trace_event(p, kEvCombined);
