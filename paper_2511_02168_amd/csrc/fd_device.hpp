@@ -86,8 +86,14 @@ __device__ __forceinline__ int split_keys_of(int S, int n)
 // contiguous stretches of the cache.
 struct WorkList {
     int x, wl, members, n_tiles, n_items;
+    int base, rem;        // block w = [block_first(w), block_first(w + 1)): base items, one more in the first rem blocks
     int first, last;      // this workgroup's block of items [first, last)
 };
+
+// First item of block w when n_items items are dealt to `members` blocks as evenly as
+// possible (32-bit arithmetic only: this is evaluated on latency-critical paths).
+__device__ __forceinline__ int block_first(int w, int base, int rem) { return w * base + min(w, rem); }
+
 
 struct Item {
     int tile, b, kvh, split, n, S;
@@ -104,8 +110,10 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     wlst.n_tiles = wlst.x < T ? (T - wlst.x + X - 1) / X : 0;
     if (p.n_splits > 0) {
         wlst.n_items = wlst.n_tiles * p.n_splits;
-        wlst.first = (int)((long long)wlst.wl * wlst.n_items / wlst.members);
-        wlst.last = (int)((long long)(wlst.wl + 1) * wlst.n_items / wlst.members);
+        wlst.base = wlst.n_items / wlst.members;
+        wlst.rem = wlst.n_items - wlst.base * wlst.members;
+        wlst.first = block_first(wlst.wl, wlst.base, wlst.rem);
+        wlst.last = block_first(wlst.wl + 1, wlst.base, wlst.rem);
         return;
     }
     // adaptive: block-wide exclusive scan of n_b over the group's tiles
@@ -134,8 +142,10 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     if (tid == kWgThreads - 1) pre[wlst.n_tiles] = scan_tmp[tid];
     __syncthreads();
     wlst.n_items = pre[wlst.n_tiles];
-    wlst.first = (int)((long long)wlst.wl * wlst.n_items / wlst.members);
-    wlst.last = (int)((long long)(wlst.wl + 1) * wlst.n_items / wlst.members);
+    wlst.base = wlst.n_items / wlst.members;
+    wlst.rem = wlst.n_items - wlst.base * wlst.members;
+    wlst.first = block_first(wlst.wl, wlst.base, wlst.rem);
+    wlst.last = block_first(wlst.wl + 1, wlst.base, wlst.rem);
 }
 
 __device__ __forceinline__ Item worklist_item(const Params& p, const WorkList& wlst, const int* pre, int e)
@@ -385,12 +395,12 @@ __device__ inline void combine_tile_unstaged(const float* plse, const float* po,
 // through LDS.  Rows are taken in ascending order within a slice and slices in ascending
 // order, so for a given partition the result does not depend on which workgroup runs this.
 // What the combining workgroup of the fused kernel knows about who wrote the tile's
-// partials: the tile's items are [t0, t0 + n) of a work list of n_items items cut into
-// `members` contiguous blocks (see WorkList); block w wrote one partial, into the slot of
-// its first item of this tile, if it holds any of the tile's items and that item's key
-// range is not empty.
+// partials: the tile's items are [t0, t0 + n) of a work list cut into `members` contiguous
+// blocks (see WorkList, block_first); block w wrote one partial, into the slot of its first
+// item of this tile, if it holds any of the tile's items and that item's key range is not
+// empty.
 struct TileSchedule {
-    int t0, n_items, members, split_keys, S;
+    int t0, base, rem, members, split_keys, S;
 };
 
 template <int BATCH>
@@ -419,15 +429,20 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     if (tid < 64) {
         int count = 0, live0 = 0;
         if (sch) {
-            // the live slots follow from the schedule: no memory access
-            const long long E = sch->n_items, M = sch->members;
-            const int t0 = sch->t0;
-            const int w_first = max(0, (int)(t0 * M / E) - 1);
-            const int w_end = min((int)M, (int)(((long long)(t0 + n) * M + E - 1) / E) + 1);
+            // the live slots follow from the schedule: no memory access.  Candidate blocks:
+            // a range that surely contains every block holding an item of [t0, t0 + n)
+            // (block w starts at or after w * base and before (w + 1) * (base + 1))
+            const int t0 = sch->t0, members = sch->members;
+            int w_first = 0, w_end = members;
+            if (sch->base > 0) {
+                w_first = max(0, (int)((float)t0 * __builtin_amdgcn_rcpf((float)(sch->base + 1))) - 1);
+                w_end = min(members, (int)((float)(t0 + n) * __builtin_amdgcn_rcpf((float)sch->base)) + 2);
+            }
 #pragma nounroll
-            for (int base = w_first; base < w_end; base += 64) {
-                const int w = base + lane;
-                const int lo = max((int)(w * E / M), t0), hi = min((int)((w + 1) * E / M), t0 + n);
+            for (int w0 = w_first; w0 < w_end; w0 += 64) {
+                const int w = w0 + lane;
+                const int lo = max(block_first(w, sch->base, sch->rem), t0);
+                const int hi = min(block_first(w + 1, sch->base, sch->rem), t0 + n);
                 const bool live = w < w_end && lo < hi && (long long)(lo - t0) * sch->split_keys < sch->S;
                 const unsigned long long mask = __ballot(live);
                 const int k = count + __popcll(mask & ((1ull << lane) - 1ull));

@@ -124,7 +124,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             __syncthreads();
             trace_event(p, kEvCounted);
             if (ss.is_last) {
-                const TileSchedule sch = {t0, wl.n_items, wl.members, c, it.S};
+                const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
                 combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, &sch);
                 if (threadIdx.x == 0)                               // re-arm for the next call
                     __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
