@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="rotating K/V copies (0 = enough to exceed 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bsp", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the read-only streaming kernel (achievable bandwidth)")
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
@@ -61,6 +62,39 @@ def time_calls(fn, n_warm, n_steps, torch):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
     return e0.elapsed_time(e1) / n_steps, wall_ms
+
+
+def per_call_percentiles(fn, n_calls, torch):
+    """p10 / median / p90 of single calls, each bracketed by its own pair of HIP events (us)."""
+    import numpy as np
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_calls)]
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        fn(i)
+        b.record()
+    torch.cuda.synchronize()
+    d = np.array([a.elapsed_time(b) * 1e3 for a, b in ev])
+    return [round(float(np.percentile(d, q)), 2) for q in (10, 50, 90)]
+
+
+def streaming_probe(fd, torch, stream):
+    """Bandwidth of a read-only kernel (the library's 128-bit non-temporal loads) over 1 GiB: GB/s."""
+    src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).fill_(1.0)
+    sink = torch.zeros(1, device="cuda", dtype=torch.int32)
+    nbytes = src.numel() * 4
+    for _ in range(3):
+        fd.fd_debug_stream_read(src, nbytes, sink, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        fd.fd_debug_stream_read(src, nbytes, sink, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    gbs = nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src
+    return gbs
 
 
 def read_traffic(workload_name):
@@ -156,6 +190,10 @@ def main():
     if not args.no_bsp:
         bsp_ms, _ = time_calls(bsp, args.warmup, args.steps, torch)
 
+    pct_fused = per_call_percentiles(fused, min(args.steps, 200), torch)
+    pct_bsp = None if args.no_bsp else per_call_percentiles(bsp, min(args.steps, 200), torch)
+    probe_gbs = None if args.no_probe else streaming_probe(fd, torch, stream)
+
     gbs = alg_bytes / (fused_ms * 1e-3) / 1e9
     rec = {
         "metric": "decode-attention us/call + achieved HBM GB/s (% of roofline), fused vs BSP",
@@ -177,6 +215,10 @@ def main():
         "us_per_call_fused_host_wall": round(fused_wall_ms * 1e3, 3),
         "us_per_call_bsp": None if bsp_ms is None else round(bsp_ms * 1e3, 3),
         "fused_over_bsp": None if bsp_ms is None else round(fused_ms / bsp_ms, 4),
+        "us_single_call_fused_p10_p50_p90": pct_fused,
+        "us_single_call_bsp_p10_p50_p90": pct_bsp,
+        "streaming_read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
+        "pct_of_streaming_read_probe": None if probe_gbs is None else round(100.0 * gbs / probe_gbs, 2),
         "pct_of_hbm_roofline": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_call": alg_bytes,
         "roofline": {"bound": "hbm", "achieved": round(gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -173,6 +173,16 @@ int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n);
 #define FD_TRACE_EVENTS 12
 int fd_debug_set_trace(fd_handle_t h, void* device_buffer, int32_t capacity_workgroups);
 
+/*
+ * Measurement aid, no handle needed: one pass of 128-bit non-temporal loads (the loads of
+ * the K/V stream) over `bytes` bytes (rounded down to 16) at src (device, 16-byte aligned),
+ * one contiguous block per workgroup, one workgroup per compute unit; nothing is written
+ * (sink, device, 4 bytes, only keeps the loads alive).  Asynchronous on `stream`.  Timing
+ * it gives the bandwidth a read-only kernel reaches on this chip, the practical ceiling
+ * for fd_decode.
+ */
+int fd_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
 /* Text of the calling thread's last error ("" if none). Never NULL. */
 const char* fd_last_error(void);
 int fd_version(void);

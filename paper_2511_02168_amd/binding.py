@@ -21,7 +21,7 @@ FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH = 100, 101, 102
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
            "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
-           "fd_debug_set_trace",
+           "fd_debug_set_trace", "fd_debug_stream_read",
            "fd_last_error", "fd_version"]
 
 
@@ -71,6 +71,8 @@ def lib():
         L.fd_debug_read_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), i32]
         L.fd_debug_set_trace.restype = ctypes.c_int
         L.fd_debug_set_trace.argtypes = [vp, vp, i32]
+        L.fd_debug_stream_read.restype = ctypes.c_int
+        L.fd_debug_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.fd_last_error.restype = ctypes.c_char_p
         L.fd_last_error.argtypes = []
         L.fd_version.restype = ctypes.c_int
@@ -149,6 +151,10 @@ FD_TRACE_EVENTS = 12
 
 def fd_debug_set_trace(h, buf, capacity_workgroups: int) -> None:
     _check(lib().fd_debug_set_trace(h, _ptr(buf), int(capacity_workgroups)))
+
+
+def fd_debug_stream_read(src, nbytes: int, sink, stream: int = 0) -> None:
+    _check(lib().fd_debug_stream_read(_ptr(src), int(nbytes), _ptr(sink), ctypes.c_void_p(stream)))
 
 
 class FlashDecode:

@@ -182,6 +182,36 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
     trace_event(p, kEvEnd);
 }
 
+
+// Measurement aid: reads `n_vec` 16-byte vectors once with the loads the K/V stream uses
+// (128-bit, non-temporal), one contiguous block per workgroup, and folds them into a
+// checksum that is practically never stored.  Its bandwidth is what a kernel that does
+// nothing but read can reach on this chip: the "achievable" line next to the 8 TB/s peak.
+__global__ __launch_bounds__(kWgThreads) void fd_stream_read_kernel(const uint4* __restrict__ src, size_t n_vec,
+                                                                    uint32_t* sink)
+{
+    constexpr int kUnroll = 16;                                // 64 KB per workgroup step
+    const size_t chunk = (size_t)kWgThreads * kUnroll;
+    const size_t n_chunks = n_vec / chunk;
+    const size_t first = blockIdx.x * n_chunks / gridDim.x, last = (blockIdx.x + 1) * n_chunks / gridDim.x;
+    uint32_t acc = 0;
+    for (size_t c = first; c < last; ++c) {
+        const uint4* p = src + c * chunk + threadIdx.x;
+        uint4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = load_stream(p + u * kWgThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    // the tail that does not fill a chunk
+    for (size_t i = n_chunks * chunk + (size_t)blockIdx.x * kWgThreads + threadIdx.x; i < n_vec;
+         i += (size_t)gridDim.x * kWgThreads) {
+        const uint4 v = load_stream(src + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u) *sink = acc;
+}
+
 }  // namespace fd
 
 // ---------------------------------------------------------------------------
@@ -553,6 +583,19 @@ int fd_debug_set_trace(fd_handle_t h, void* device_buffer, int32_t capacity_work
     if ((uintptr_t)device_buffer & 7) return fail(FD_ERR_INVALID_ARG, "trace buffer must be 8-byte aligned");
     h->trace = (unsigned long long*)device_buffer;
     h->trace_capacity = device_buffer ? capacity_workgroups : 0;
+    return FD_OK;
+}
+
+int fd_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream)
+{
+    if (!src || !sink || bytes < 16) return fail(FD_ERR_INVALID_ARG, "src, sink must be non-NULL and bytes >= 16");
+    if ((uintptr_t)src & 15) return fail(FD_ERR_INVALID_ARG, "src must be 16-byte aligned");
+    int dev = 0, cus = 0;
+    FD_HIP(hipGetDevice(&dev));
+    FD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    hipLaunchKernelGGL(fd::fd_stream_read_kernel, dim3(cus), dim3(fd::kWgThreads), 0, (hipStream_t)stream,
+                       (const uint4*)src, bytes / 16, sink);
+    FD_HIP(hipGetLastError());
     return FD_OK;
 }
 

@@ -364,3 +364,44 @@ def test_argument_errors_on_device():
                 fd.fd_set_option(dec.h, key, bad)
             assert e.value.code == fd.FD_ERR_INVALID_ARG
         assert fd.fd_get_option(dec.h, fd.FD_INFO_NUM_CUS) == 256
+
+
+def test_reset_trace_and_stream_probe_entry_points():
+    """The maintenance / measurement entry points: fd_reset re-zeroes the counters, the
+    timeline trace records ordered milestones for every workgroup and leaves results
+    unchanged, the read-only streaming kernel runs and validates its arguments."""
+    wl = _generic(2, 16, 2, 3000, 777)
+    say("case fd_reset, fd_debug_set_trace, fd_debug_stream_read")
+    inp = fi.make_inputs(wl, "cuda")
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=16) as dec:
+        out0, lse0 = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+        fd.fd_reset(dec.h)
+        torch.cuda.synchronize()
+        assert all(c == 0 for c in fd.fd_debug_read_counters(dec.h, wl.B * wl.Hkv))
+        grid_cap = 1024
+        tr = torch.zeros(grid_cap, fd.FD_TRACE_EVENTS, device="cuda", dtype=torch.int64)
+        fd.fd_debug_set_trace(dec.h, tr, grid_cap)
+        out1, lse1 = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+        torch.cuda.synchronize()
+        fd.fd_debug_set_trace(dec.h, None, 0)
+        grid = fd.fd_get_option(dec.h, fd.FD_INFO_LAST_GRID)
+        t = tr[:grid].cpu().numpy()
+        assert (t[:, 0] > 0).all() and (t[:, 7] >= t[:, 0]).all(), "every workgroup records start <= end"
+        busy = t[:, 2] > 0
+        assert busy.any() and (t[busy, 2] >= t[busy, 1]).all() and (t[busy, 1] >= t[busy, 0]).all()
+        assert (tr[grid:] == 0).all()
+        assert torch.equal(out0.view(torch.int32), out1.view(torch.int32)) and torch.equal(lse0, lse1)
+        out2, _ = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+        torch.cuda.synchronize()
+        assert torch.equal(out0.view(torch.int32), out2.view(torch.int32))
+    src = torch.ones((1 << 20) + 5, device="cuda", dtype=torch.float32)       # ragged tail: not a whole chunk
+    sink = torch.zeros(1, device="cuda", dtype=torch.int32)
+    fd.fd_debug_stream_read(src, src.numel() * 4, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
+    with pytest.raises(fd.FdError) as e:
+        fd.fd_debug_stream_read(None, 1024, sink)
+    assert e.value.code == fd.FD_ERR_INVALID_ARG
+    with pytest.raises(fd.FdError) as e:
+        fd.fd_debug_stream_read(src[1:], 1024, sink)                           # 4-byte aligned only
+    assert e.value.code == fd.FD_ERR_INVALID_ARG
