@@ -135,3 +135,39 @@ def merge(part_o: np.ndarray, part_lse: np.ndarray):
     if rc != 0:
         raise ValueError("fd_oracle_merge rejected its arguments")
     return o, float(lse[0])
+
+
+def decode_paged(q: np.ndarray, k_pages: np.ndarray, v_pages: np.ndarray, block_table: np.ndarray,
+                 seq_lens: np.ndarray, scale: float = 0.0, n_threads: int = 0):
+    """The same attention over a paged KV cache, by its definition: key j of sequence b is
+    row j % page_size of page block_table[b, j // page_size].
+
+    q [B,Hq,D]; k_pages/v_pages [num_pages,Hkv,page_size,D] as bf16 bits; block_table
+    [B,max_pages] int; seq_lens [B].  Every sequence's keys are copied out of their pages
+    into a contiguous cache, one row at a time, and handed to decode(); table entries of
+    pages a sequence does not reach are never looked at.
+    """
+    q = _u16(q, 3, "q")
+    kp = _u16(k_pages, 4, "k_pages")
+    vp = _u16(v_pages, 4, "v_pages")
+    if kp.shape != vp.shape:
+        raise ValueError("k_pages and v_pages differ in shape")
+    num_pages, Hkv, page_size, D = kp.shape
+    B = q.shape[0]
+    bt = np.asarray(block_table)
+    sl = np.asarray(seq_lens, dtype=np.int64)
+    if bt.ndim != 2 or bt.shape[0] != B or sl.shape != (B,):
+        raise ValueError("block_table must be [B, max_pages], seq_lens [B]")
+    if (sl < 0).any() or (sl > bt.shape[1] * page_size).any():
+        raise ValueError("a sequence is longer than its block table")
+    S_max = max(1, int(sl.max()) if B else 1)
+    k = np.zeros((B, Hkv, S_max, D), dtype=np.uint16)
+    v = np.zeros((B, Hkv, S_max, D), dtype=np.uint16)
+    for b in range(B):
+        for j in range(int(sl[b])):
+            page = int(bt[b, j // page_size])
+            if not 0 <= page < num_pages:
+                raise ValueError(f"block_table[{b}, {j // page_size}] = {page} is not a page")
+            k[b, :, j, :] = kp[page, :, j % page_size, :]
+            v[b, :, j, :] = vp[page, :, j % page_size, :]
+    return decode(q, k, v, sl.astype(np.int32), scale=scale, n_threads=n_threads)

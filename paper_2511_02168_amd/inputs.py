@@ -166,6 +166,47 @@ def make_inputs(wl: Workload, device="cpu", S_max: Optional[int] = None,
     return Inputs(q=q, k=k, v=v, seq_lens=sl, wl=wl)
 
 
+@dataclass
+class PagedInputs:
+    q: torch.Tensor            # [B, Hq, D] bf16
+    k_pages: torch.Tensor      # [num_pages, Hkv, page_size, D] bf16
+    v_pages: torch.Tensor      # [num_pages, Hkv, page_size, D] bf16
+    block_table: torch.Tensor  # [B, max_pages_per_seq] int32
+    seq_lens: torch.Tensor     # [B] int32
+    page_size: int = 16
+
+
+def make_paged(inp: Inputs, page_size: int, seed: int = 0) -> PagedInputs:
+    """Scatters a contiguous cache into a page pool: the pages a sequence reaches get distinct
+    pool slots in a seeded random order; the pool holds one extra page of NaN, and every table
+    entry past a sequence's last page points at it (a read through such an entry poisons the
+    result).  Rows of the last page past seq_lens[b] keep what the contiguous cache held there.
+    """
+    B, Hkv, S, D = inp.k.shape
+    dev = inp.k.device
+    max_pages = -(-S // page_size)
+    sl = inp.seq_lens.cpu().tolist()
+    used = [-(-s // page_size) for s in sl]
+    n_used = sum(used)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(1000003 * page_size + seed)
+    slots = torch.randperm(n_used, generator=gen).tolist()
+    nan_page = n_used
+    k_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=torch.bfloat16)
+    v_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=torch.bfloat16)
+    table = torch.full((B, max_pages), nan_page, dtype=torch.int32)
+    it = iter(slots)
+    for b in range(B):
+        for pg in range(used[b]):
+            slot = next(it)
+            table[b, pg] = slot
+            lo, hi = pg * page_size, min((pg + 1) * page_size, S)
+            k_pages[slot, :, : hi - lo] = inp.k[b, :, lo:hi]
+            v_pages[slot, :, : hi - lo] = inp.v[b, :, lo:hi]
+    return PagedInputs(q=inp.q, k_pages=k_pages, v_pages=v_pages, block_table=table.to(dev),
+                       seq_lens=inp.seq_lens, page_size=page_size)
+
+
 def algorithmic_bytes(wl: Workload, seq_lens) -> int:
     """Bytes the method must move: K and V rows of every live key once, q in, out + lse out."""
     lens = [int(s) for s in seq_lens]

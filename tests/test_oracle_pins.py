@@ -14,6 +14,7 @@ import torch
 
 import oracle
 from paper_2511_02168_amd.inputs import f32_to_bf16_bits, bf16_bits_to_f32
+from paper_2511_02168_amd import inputs as fi
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -360,3 +361,99 @@ def test_bf16_helpers_round_to_nearest_even():
     rng = np.random.default_rng(0)
     y = rng.standard_normal(10000).astype(np.float32)
     assert np.array_equal(f32_to_bf16_bits(y), torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+
+
+# ---- paged KV cache: the oracle's gather against things fixed from outside it --------------
+
+def _tiny_paged(seed, B=2, Hq=4, Hkv=2, D=8, page_size=4, lens=(7, 10)):
+    rng = np.random.default_rng(seed)
+    max_pages = -(-max(lens) // page_size)
+    S = max_pages * page_size
+    q = fi.f32_to_bf16_bits(rng.standard_normal((B, Hq, D)).astype(np.float32))
+    k = fi.f32_to_bf16_bits(rng.standard_normal((B, Hkv, S, D)).astype(np.float32))
+    v = fi.f32_to_bf16_bits(rng.standard_normal((B, Hkv, S, D)).astype(np.float32))
+    return q, k, v, np.array(lens, dtype=np.int32), page_size, max_pages
+
+
+def _to_pages(k, v, page_size, order):
+    """Cuts [B,Hkv,S,D] into pages and stores page (b, p) at pool slot order[b * max_pages + p]."""
+    B, Hkv, S, D = k.shape
+    max_pages = S // page_size
+    kp = np.zeros((B * max_pages, Hkv, page_size, D), dtype=np.uint16)
+    vp = np.zeros_like(kp)
+    bt = np.zeros((B, max_pages), dtype=np.int32)
+    for b in range(B):
+        for p in range(max_pages):
+            slot = order[b * max_pages + p]
+            bt[b, p] = slot
+            kp[slot] = k[b, :, p * page_size:(p + 1) * page_size]
+            vp[slot] = v[b, :, p * page_size:(p + 1) * page_size]
+    return kp, vp, bt
+
+
+def test_paged_with_identity_table_is_the_contiguous_result():
+    q, k, v, sl, ps, mp = _tiny_paged(11)
+    kp, vp, bt = _to_pages(k, v, ps, list(range(k.shape[0] * mp)))
+    o_ref, l_ref = oracle.decode(q, k, v, sl)
+    o, l = oracle.decode_paged(q, kp, vp, bt, sl)
+    assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
+
+
+def test_paged_result_does_not_depend_on_where_pages_live():
+    q, k, v, sl, ps, mp = _tiny_paged(12, lens=(9, 16))
+    n = k.shape[0] * mp
+    o_ref, l_ref = oracle.decode(q, k, v, sl)
+    for seed in (1, 2, 3):
+        order = np.random.default_rng(seed).permutation(n).tolist()
+        kp, vp, bt = _to_pages(k, v, ps, order)
+        o, l = oracle.decode_paged(q, kp, vp, bt, sl)
+        assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
+
+
+def test_paged_against_pure_python_indexing():
+    """Brute force with the page arithmetic written inline: score_j uses row j % ps of page bt[b][j // ps]."""
+    q, k, v, sl, ps, mp = _tiny_paged(13, B=1, Hq=2, Hkv=1, D=4, page_size=2, lens=(5,))
+    order = [2, 0, 1]
+    kp, vp, bt = _to_pages(k, v, ps, order)
+    o, l = oracle.decode_paged(q, kp, vp, bt, sl)
+    qf, kf, vf = (fi.bf16_bits_to_f32(x).astype(np.float64) for x in (q, kp, vp))
+    for h in range(2):
+        scores = []
+        for j in range(5):
+            row = kf[bt[0, j // ps], 0, j % ps]
+            scores.append(sum(qf[0, h, d] * row[d] for d in range(4)) / math.sqrt(4))
+        m = max(scores)
+        w = [math.exp(s - m) for s in scores]
+        tot = sum(w)
+        for d in range(4):
+            ref = sum(w[j] * vf[bt[0, j // ps], 0, j % ps, d] for j in range(5)) / tot
+            assert abs(o[0, h, d] - ref) < 1e-12
+        assert abs(l[0, h] - (m + math.log(tot))) < 1e-12
+
+
+def test_paged_ignores_table_entries_past_the_sequence_and_rejects_bad_ones():
+    q, k, v, sl, ps, mp = _tiny_paged(14, lens=(3, 6))
+    kp, vp, bt = _to_pages(k, v, ps, list(range(k.shape[0] * mp)))
+    o_ref, l_ref = oracle.decode_paged(q, kp, vp, bt, sl)
+    bt2 = bt.copy()
+    bt2[0, 1:] = 10 ** 6          # sequence 0 has 3 keys = 1 page: later entries are never read
+    o, l = oracle.decode_paged(q, kp, vp, bt2, sl)
+    assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
+    bt2[1, 0] = kp.shape[0]       # a page that sequence 1 does use
+    with pytest.raises(ValueError):
+        oracle.decode_paged(q, kp, vp, bt2, sl)
+
+
+def test_make_paged_round_trips_through_the_oracle():
+    """The input generator's scatter and the oracle's gather are written independently
+    (torch slices there, row-by-row numpy copies here): together they must be the identity."""
+    import torch
+    wl = fi.Workload("paged_rt", 77, B=3, Hq=4, Hkv=2, S_max=50, n_splits=0, ragged=True)
+    inp = fi.make_inputs(wl, "cpu")
+    o_ref, l_ref = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.numpy())
+    for ps in (16, 32):
+        pg = fi.make_paged(inp, ps, seed=5)
+        assert pg.k_pages.shape[2] == ps and torch.isnan(pg.k_pages[-1].float()).all()
+        o, l = oracle.decode_paged(fi.bits(pg.q), fi.bits(pg.k_pages), fi.bits(pg.v_pages),
+                                   pg.block_table.numpy(), pg.seq_lens.numpy())
+        assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
