@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define FD_VERSION 100
+#define FD_VERSION 110
 
 enum {
     FD_OK = 0,
@@ -126,6 +126,34 @@ int fd_decode(fd_handle_t h, const void* q, const void* k_cache, const void* v_c
 int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
                   const int32_t* seq_lens, float* out, float* lse, int32_t n_splits,
                   void* stream);
+
+/*
+ * The same computation over a PAGED KV cache (the layout decode servers use).
+ *
+ *   k_pages, v_pages  [num_pages, Hkv, page_size, D] bf16, device, 16-byte aligned: the
+ *                     page pool; the page_size rows of one (page, KV head) are contiguous
+ *   block_table       [B, pages_per_seq] int32, device: key j of sequence b is row
+ *                     j % page_size of pool page block_table[b][j / page_size].  Only
+ *                     entries of pages below ceil(seq_lens[b] / page_size) are looked at;
+ *                     entries outside [0, num_pages) are clamped into that range, so that
+ *                     no access ever leaves the pool (the result is then meaningless)
+ *   page_size         power of two, 16 .. 65536 keys
+ *   pages_per_seq     row length of block_table; pages_per_seq * page_size >= S_max
+ *   everything else   as for fd_decode (S_max of the handle bounds seq_lens[b])
+ *
+ * Rows of a sequence's last page at or past seq_lens[b] are never read.  The MFMA kernel
+ * serves every group size here (FD_OPT_PATH = 1 is FD_ERR_UNSUPPORTED): each wave looks up
+ * the page of each of its 16-key blocks; page numbers are staged in LDS 256 blocks ahead,
+ * so the streaming loop is the contiguous one plus one LDS read per block.
+ * fd_decode_paged_bsp is the two-kernel baseline, bitwise equal as above.
+ */
+int fd_decode_paged(fd_handle_t h, const void* q, const void* k_pages, const void* v_pages,
+                    const int32_t* block_table, int32_t page_size, int32_t pages_per_seq, int32_t num_pages,
+                    const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream);
+int fd_decode_paged_bsp(fd_handle_t h, const void* q, const void* k_pages, const void* v_pages,
+                        const int32_t* block_table, int32_t page_size, int32_t pages_per_seq,
+                        int32_t num_pages, const int32_t* seq_lens, float* out, float* lse, int32_t n_splits,
+                        void* stream);
 
 /*
  * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.

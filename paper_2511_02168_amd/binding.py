@@ -20,7 +20,7 @@ FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES = 1, 2, 3,
 FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH = 100, 101, 102
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
-           "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
+           "fd_decode_paged", "fd_decode_paged_bsp", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
            "fd_debug_set_trace", "fd_debug_stream_read",
            "fd_last_error", "fd_version"]
 
@@ -71,6 +71,10 @@ def lib():
         L.fd_debug_read_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), i32]
         L.fd_debug_set_trace.restype = ctypes.c_int
         L.fd_debug_set_trace.argtypes = [vp, vp, i32]
+        for name in ("fd_decode_paged", "fd_decode_paged_bsp"):
+            fn = getattr(L, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, i32, vp]
         L.fd_debug_stream_read.restype = ctypes.c_int
         L.fd_debug_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.fd_last_error.restype = ctypes.c_char_p
@@ -106,6 +110,16 @@ def fd_create(cfg: fd_config) -> ctypes.c_void_p:
 
 def fd_destroy(h) -> None:
     _check(lib().fd_destroy(h))
+
+
+def fd_decode_paged(h, q, k_pages, v_pages, block_table, page_size: int, seq_lens, out, lse, n_splits: int,
+                    stream: int = 0, bsp: bool = False) -> None:
+    """k_pages / v_pages [num_pages, Hkv, page_size, D]; block_table [B, pages_per_seq] int32."""
+    fn = lib().fd_decode_paged_bsp if bsp else lib().fd_decode_paged
+    _check(fn(h, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), int(page_size),
+              0 if block_table is None else int(block_table.shape[1]), int(k_pages.shape[0]), _ptr(seq_lens),
+              _ptr(out), _ptr(lse),
+              int(n_splits), ctypes.c_void_p(stream)))
 
 
 def fd_reset(h, stream: int = 0) -> None:
@@ -209,4 +223,25 @@ class FlashDecode:
             stream = torch.cuda.current_stream().cuda_stream
         fn = fd_decode_bsp if bsp else fd_decode
         fn(self.h, q, k, v, seq_lens, out, lse, n_splits, stream)
+        return out, lse
+
+    def decode_paged(self, q, k_pages, v_pages, block_table, page_size: int, seq_lens, n_splits: int,
+                     out=None, lse=None, bsp: bool = False, stream: Optional[int] = None, want_lse: bool = True):
+        import torch
+        c = self.cfg
+        if out is None:
+            out = torch.empty(c.B, c.Hq, c.D, device=q.device, dtype=torch.float32)
+        if lse is None and want_lse:
+            lse = torch.empty(c.B, c.Hq, device=q.device, dtype=torch.float32)
+        assert k_pages.is_cuda and v_pages.is_cuda and block_table.is_cuda and q.is_cuda and seq_lens.is_cuda
+        assert k_pages.dtype == torch.bfloat16 and v_pages.dtype == torch.bfloat16 and block_table.dtype == torch.int32
+        assert k_pages.shape == v_pages.shape and k_pages.is_contiguous() and v_pages.is_contiguous()
+        assert tuple(k_pages.shape[1:]) == (c.Hkv, page_size, c.D)
+        assert block_table.dim() == 2 and block_table.shape[0] == c.B and block_table.is_contiguous()
+        assert tuple(q.shape) == (c.B, c.Hq, c.D) and q.is_contiguous() and q.dtype == torch.bfloat16
+        assert tuple(seq_lens.shape) == (c.B,) and seq_lens.dtype == torch.int32 and seq_lens.is_contiguous()
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        fd_decode_paged(self.h, q, k_pages, v_pages, block_table, page_size, seq_lens, out, lse, n_splits,
+                        stream, bsp=bsp)
         return out, lse

@@ -27,8 +27,12 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 struct Params {
     const uint16_t* q;        // [B, Hq, D] bf16
-    const uint16_t* k;        // [B, Hkv, S_max, D] bf16
-    const uint16_t* v;        // [B, Hkv, S_max, D] bf16
+    const uint16_t* k;        // [B, Hkv, S_max, D] bf16, or the page pool [num_pages, Hkv, page_size, D]
+    const uint16_t* v;        // like k
+    const int32_t* block_table;  // paged cache: [B, pages_per_seq], pool page of each logical page; null = contiguous
+    int32_t page_shift;       // log2(page_size)
+    int32_t pages_per_seq;
+    int32_t num_pages;
     const int32_t* seq_lens;  // [B]
     float* out;               // [B, Hq, D]
     float* lse;               // [B, Hq] or null

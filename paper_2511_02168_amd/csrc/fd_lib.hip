@@ -324,7 +324,7 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     static thread_local int granted_device[2] = {-1, -1};
     int dev = 0;
     FD_HIP(hipGetDevice(&dev));
-    const size_t ring = (size_t)fd::mfma_ring_bytes(NST);
+    const size_t ring = (size_t)fd::mfma_lds_bytes(NST);      // ring + page-number slots
     if (granted_device[fused] != dev) {
         if (fused)
             FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true, CB>,
@@ -344,8 +344,14 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
+// Paged-cache arguments of a call; table == nullptr for the contiguous layout.
+struct PagedArgs {
+    const int32_t* table;
+    int32_t page_size, pages_per_seq, num_pages;
+};
+
 int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, const int32_t* seq_lens, float* out,
-                  float* lse, int32_t n_splits, void* stream, bool fused)
+                  float* lse, int32_t n_splits, void* stream, bool fused, const PagedArgs& pg = PagedArgs{nullptr, 0, 0, 0})
 {
     int rc = check_handle(h);
     if (rc) return rc;
@@ -356,6 +362,17 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         return fail(FD_ERR_INVALID_ARG, "n_splits must be in 0..max_splits=%d (got %d)", h->cfg.max_splits, n_splits);
     const fd_config& c = h->cfg;
     const int tiles = c.B * c.Hkv;
+    int page_shift = 0;
+    if (pg.table) {
+        if (pg.page_size < 16 || pg.page_size > 65536 || (pg.page_size & (pg.page_size - 1)))
+            return fail(FD_ERR_INVALID_ARG, "page_size must be a power of two in 16..65536 (got %d)", pg.page_size);
+        if (pg.num_pages <= 0 || pg.pages_per_seq <= 0)
+            return fail(FD_ERR_INVALID_ARG, "num_pages and pages_per_seq must be positive");
+        if ((long long)pg.pages_per_seq * pg.page_size < c.S_max)
+            return fail(FD_ERR_INVALID_ARG, "block table rows cover %lld keys, fewer than S_max = %d",
+                        (long long)pg.pages_per_seq * pg.page_size, c.S_max);
+        while ((1 << page_shift) < pg.page_size) ++page_shift;
+    }
 
     // which kernel: measured crossover on MI355X.  From 4 query heads per KV head on, the
     // MFMA kernel wins (its K/V stream needs no registers, the VALU kernel's does and runs
@@ -363,6 +380,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     // and the VALU kernel is as fast or faster.
     const int G = h->G;
     int path = h->opt_path;
+    if (pg.table) {
+        // only the MFMA kernel follows a block table; it handles every group size
+        if (path == 1) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel does not read paged caches");
+        path = 2;
+    }
     if (path == 0) path = G >= 4 ? 2 : 1;
     if (path == 1 && G > 8) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for Hq/Hkv <= 8 (got %d)", G);
 
@@ -391,6 +413,10 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.q = (const uint16_t*)q;
     p.k = (const uint16_t*)k;
     p.v = (const uint16_t*)v;
+    p.block_table = pg.table;
+    p.page_shift = page_shift;
+    p.pages_per_seq = pg.pages_per_seq;
+    p.num_pages = pg.num_pages;
     p.seq_lens = seq_lens;
     p.out = out;
     p.lse = lse;
@@ -511,6 +537,24 @@ int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void*
                   float* out, float* lse, int32_t n_splits, void* stream)
 {
     return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, false);
+}
+
+int fd_decode_paged(fd_handle_t h, const void* q, const void* k_pages, const void* v_pages, const int32_t* block_table,
+                    int32_t page_size, int32_t pages_per_seq, int32_t num_pages, const int32_t* seq_lens, float* out,
+                    float* lse, int32_t n_splits, void* stream)
+{
+    if (!block_table) return fail(FD_ERR_INVALID_ARG, "block_table must be non-NULL");
+    return decode_common(h, q, k_pages, v_pages, seq_lens, out, lse, n_splits, stream, true,
+                         PagedArgs{block_table, page_size, pages_per_seq, num_pages});
+}
+
+int fd_decode_paged_bsp(fd_handle_t h, const void* q, const void* k_pages, const void* v_pages,
+                        const int32_t* block_table, int32_t page_size, int32_t pages_per_seq, int32_t num_pages,
+                        const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream)
+{
+    if (!block_table) return fail(FD_ERR_INVALID_ARG, "block_table must be non-NULL");
+    return decode_common(h, q, k_pages, v_pages, seq_lens, out, lse, n_splits, stream, false,
+                         PagedArgs{block_table, page_size, pages_per_seq, num_pages});
 }
 
 int fd_set_option(fd_handle_t h, int32_t key, int32_t value)

@@ -35,6 +35,10 @@ constexpr int kMfStageBytes = 2 * kMfHalfBytes;             // 8 KB
 constexpr int kMfRows = 16;                                 // MFMA tile rows = max heads per KV head
 
 __host__ __device__ constexpr int mfma_ring_bytes(int nst) { return kWaves * nst * kMfStageBytes; }
+// Paged cache: page numbers of a wave's next blocks, fetched kMfPageSlots blocks at a time
+// into LDS behind the ring, so that the streaming loop itself never touches the block table.
+constexpr int kMfPageSlots = 256;    // 16K keys per workgroup between refills; 4 KB of LDS
+__host__ __device__ constexpr int mfma_lds_bytes(int nst) { return mfma_ring_bytes(nst) + kWaves * kMfPageSlots * 4; }
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -51,6 +55,15 @@ __device__ __forceinline__ void dma_row4(uint32_t lds_addr, const void* gbase, u
                  :
                  : "s"(lds_addr), "v"(voff), "s"(gbase)
                  : "memory", "m0");
+}
+
+// The same pointer, held in scalar registers (the value must already be wave-uniform).
+__device__ __forceinline__ const uint16_t* scalar_ptr(const uint16_t* p)
+{
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint16_t*>((uintptr_t)(((uint64_t)hi << 32) | lo));
 }
 
 template <int N>
@@ -85,17 +98,16 @@ struct MfmaState {
     f32x4_t acc[8];     // O^T: block db, element e = dim 16*db + 4*(lane>>4) + e of head (lane & 15)
 };
 
-// Requests the 16 keys [kb, kb+16) of K and V into one stage.  Rows at or past
-// j1 re-read row j1-1 (a live row); their scores are masked later.
+// Requests the 16 keys [kb, kb+16) of K and V, whose rows start at kp / vp (wave-uniform),
+// into one stage.  Rows at or past j1 re-read row j1-1 (a live row of the same block);
+// their scores are masked later.
 // LDS layout of a half stage: row r (0..15) at r*256, its 16-byte chunk c stored at
 // position c ^ r.
-__device__ __forceinline__ void mfma_issue_stage(uint32_t lds_stage, const uint16_t* kbase, const uint16_t* vbase,
+__device__ __forceinline__ void mfma_issue_stage(uint32_t lds_stage, const uint16_t* kp, const uint16_t* vp,
                                                  int kb, int j1, int lane)
 {
     const int rsub = lane >> 4, pos = lane & 15;
     const bool full = kb + kMfBlockKeys <= j1;
-    const uint16_t* kp = kbase + (size_t)kb * kD;
-    const uint16_t* vp = vbase + (size_t)kb * kD;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = 4 * i + rsub;                       // row of the block this lane fills
@@ -193,7 +205,9 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     const int G = p.G;
     const int head = lane & 15, kg = lane >> 4;
 
-    const size_t row0 = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
+    // contiguous cache: the tile's rows; paged cache: looked up per block, see below
+    const bool paged = p.block_table != nullptr;
+    const size_t row0 = paged ? 0 : ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
     const uint16_t* kbase = p.k + row0 * kD;
     const uint16_t* vbase = p.v + row0 * kD;
 
@@ -208,6 +222,7 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     const int mine = wave < n_blocks ? (n_blocks - wave + kWaves - 1) / kWaves : 0;
     char* my_ring = ring + wave * (NST * kMfStageBytes);
     const uint32_t my_ring_lds = lds_address(my_ring);
+    int* my_pages = reinterpret_cast<int*>(ring + mfma_ring_bytes(NST)) + wave * kMfPageSlots;
     const float sl2 = p.scale_log2;
     constexpr int P = NST - 1;                            // stages in flight ahead of the one being consumed
 
@@ -223,23 +238,51 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             qb[t] = __builtin_bit_cast(bf16x8_t, v);
         }
     }
-    for (int s = 0; s < P && s < mine; ++s)
-        mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kbase, vbase, j0 + (wave + kWaves * s) * kMfBlockKeys, j1,
-                         lane);
-    // Make the compiler wait for the q loads HERE: the loop below must contain no
-    // compiler-generated vmcnt wait, which would also drain the stage loads the loop
-    // keeps in flight (they are issued from inline asm, invisible to its counter).
-    asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
-    for (int s = 0; s < mine; ++s) {
-        if (s + P < mine)
-            mfma_issue_stage(my_ring_lds + ((s + P) % NST) * kMfStageBytes, kbase, vbase,
-                             j0 + (wave + kWaves * (s + P)) * kMfBlockKeys, j1, lane);
-        wait_stages_in_flight(min(P, mine - 1 - s));
-        if (s == 0) trace_event(p, kEvFirstStage);
-        const int kb = j0 + (wave + kWaves * s) * kMfBlockKeys;
-        const char* stage = my_ring + (s % NST) * kMfStageBytes;
-        if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
-        else mfma_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+
+    // The wave's blocks are streamed in chunks: the whole range at once for a contiguous
+    // cache; kMfPageSlots blocks at a time for a paged one, whose page numbers are fetched
+    // into LDS before the chunk starts (the pipeline is empty then, so these ordinary
+    // loads disturb nothing).  The softmax state carries across chunks.
+    const int chunk_blocks = paged ? kMfPageSlots : max(mine, 1);
+    for (int c0 = 0; c0 < mine; c0 += chunk_blocks) {
+        const int cmine = min(chunk_blocks, mine - c0);
+        if (paged) {
+            const int32_t* row = p.block_table + (size_t)b * p.pages_per_seq;
+            for (int i = lane; i < cmine; i += 64) {
+                const int kb = j0 + (wave + kWaves * (c0 + i)) * kMfBlockKeys;
+                const int pg = row[kb >> p.page_shift];
+                my_pages[i] = min(max(pg, 0), p.num_pages - 1);      // never leave the pool
+            }
+        }
+        // requests stage `s` of this chunk into its ring slot
+        const auto issue = [&](int s) {
+            const int kb = j0 + (wave + kWaves * (c0 + s)) * kMfBlockKeys;
+            const uint16_t *kp, *vp;
+            if (paged) {
+                const int pg = __builtin_amdgcn_readfirstlane(my_pages[s]);
+                const size_t first_row = (((size_t)pg * p.Hkv + kvh) << p.page_shift) + (kb & ((1 << p.page_shift) - 1));
+                kp = p.k + first_row * kD;
+                vp = p.v + first_row * kD;
+            } else {
+                kp = kbase + (size_t)kb * kD;
+                vp = vbase + (size_t)kb * kD;
+            }
+            mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, scalar_ptr(kp), scalar_ptr(vp), kb, j1, lane);
+        };
+        for (int s = 0; s < P && s < cmine; ++s) issue(s);
+        // Make the compiler wait for the q loads HERE: the loop below must contain no
+        // compiler-generated vmcnt wait, which would also drain the stage loads the loop
+        // keeps in flight (they are issued from inline asm, invisible to its counter).
+        asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
+        for (int s = 0; s < cmine; ++s) {
+            if (s + P < cmine) issue(s + P);
+            wait_stages_in_flight(min(P, cmine - 1 - s));
+            if (c0 + s == 0) trace_event(p, kEvFirstStage);
+            const int kb = j0 + (wave + kWaves * (c0 + s)) * kMfBlockKeys;
+            const char* stage = my_ring + (s % NST) * kMfStageBytes;
+            if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
+            else mfma_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+        }
     }
 
     trace_event(p, kEvLoopEnd);

@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_is_built_and_loads():
     assert os.path.exists(fd.LIB_PATH), "run `python -m paper_2511_02168_amd.build` first"
-    assert fd.fd_version() == 100
+    assert fd.fd_version() == 110
 
 
 def test_every_declared_symbol_is_exported():

@@ -405,3 +405,98 @@ def test_reset_trace_and_stream_probe_entry_points():
     with pytest.raises(fd.FdError) as e:
         fd.fd_debug_stream_read(src[1:], 1024, sink)                           # 4-byte aligned only
     assert e.value.code == fd.FD_ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------- paged KV cache
+
+def _paged_parity(wl, page_size, n_values, what, max_splits=8, seed=0):
+    inp = fi.make_inputs(wl, "cuda")
+    pg = fi.make_paged(inp, page_size, seed=seed)
+    ref_o, ref_l = oracle.decode_paged(fi.bits(pg.q), fi.bits(pg.k_pages), fi.bits(pg.v_pages),
+                                       pg.block_table.cpu().numpy(), pg.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max_splits) as dec:
+        for n in n_values:
+            fd.fd_debug_poison_workspace(dec.h)
+            out_f, lse_f = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, page_size, pg.seq_lens, n)
+            out_b, lse_b = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, page_size, pg.seq_lens, n,
+                                            bsp=True)
+            out_c, lse_c = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n) if wl.Hq // wl.Hkv >= 4 else (None, None)
+            torch.cuda.synchronize()
+            assert fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH) == 2 or out_c is None
+            assert torch.equal(out_f.view(torch.int32), out_b.view(torch.int32)), "paged fused != paged BSP"
+            assert torch.equal(lse_f.view(torch.int32), lse_b.view(torch.int32))
+            if out_c is not None:      # same kernel, same partition, same key order: the layout must not change a bit
+                assert torch.equal(out_f.view(torch.int32), out_c.view(torch.int32)), "paged != contiguous"
+                assert torch.equal(lse_f.view(torch.int32), lse_c.view(torch.int32))
+            eo = check_out(out_f.cpu().numpy(), ref_o, f"{what} n={n}")
+            el = check_lse(lse_f.cpu().numpy(), ref_l, f"{what} n={n}")
+            say(f"  {what} n={n}: max |out err| {eo:.2e}, max |lse err| {el:.2e}")
+
+
+@pytest.mark.parametrize("page_size", [16, 32, 64, 128, 256, 1024])
+def test_paged_cache_every_page_size(page_size):
+    wl = _generic(3, 16, 2, 2500, 600 + page_size, ragged=True)
+    say(f"case paged cache, page_size={page_size}, G=8, ragged S<=2500, n_splits 1, 5, adaptive")
+    _paged_parity(wl, page_size, (1, 5, 0), f"paged ps={page_size}")
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 7, 8, 12, 16])
+def test_paged_cache_every_group_size(G):
+    wl = _generic(2, 2 * G, 2, 1111, 650 + G, ragged=True)
+    say(f"case paged cache, page_size=16, G={G}, ragged S<=1111")
+    _paged_parity(wl, 16, (3, 0), f"paged G={G}")
+
+
+def test_paged_cache_long_range_refills_its_page_slots():
+    """One workgroup-range longer than the 256 page-number slots per wave (16K keys): the
+    stream is refilled mid-range and the softmax state carries across."""
+    wl = _generic(1, 8, 1, 70000, 700)
+    say("case paged cache, one sequence of 70000 keys, n_splits=1 and 2, page_size 16 and 128")
+    for ps in (16, 128):
+        _paged_parity(wl, ps, (1, 2), f"paged long ps={ps}", max_splits=2, seed=ps)
+
+
+def test_paged_cache_short_and_empty_sequences():
+    wl = _generic(5, 8, 2, 300, 710)
+    say("case paged cache, seq_lens = [0, 1, 300, 16, 17]")
+    inp = fi.make_inputs(wl, "cuda")
+    inp.seq_lens = torch.tensor([0, 1, 300, 16, 17], dtype=torch.int32, device="cuda")
+    pg = fi.make_paged(inp, 16, seed=3)
+    ref_o, ref_l = oracle.decode_paged(fi.bits(pg.q), fi.bits(pg.k_pages), fi.bits(pg.v_pages),
+                                       pg.block_table.cpu().numpy(), pg.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=4) as dec:
+        for n in (0, 1, 4):
+            out, lse = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, 16, pg.seq_lens, n)
+            torch.cuda.synchronize()
+            check_out(out.cpu().numpy(), ref_o, f"paged short n={n}")
+            check_lse(lse.cpu().numpy(), ref_l, f"paged short n={n}")
+
+
+def test_paged_argument_errors():
+    say("case paged argument validation")
+    with fd.FlashDecode(1, 8, 2, 1024, max_splits=4) as dec:
+        q = torch.zeros(1, 8, 128, device="cuda", dtype=torch.bfloat16)
+        pool = torch.zeros(64, 2, 16, 128, device="cuda", dtype=torch.bfloat16)
+        table = torch.zeros(1, 64, device="cuda", dtype=torch.int32)
+        sl = torch.full((1,), 1024, device="cuda", dtype=torch.int32)
+        out = torch.empty(1, 8, 128, device="cuda")
+        for bad_ps in (8, 24, 0):
+            with pytest.raises(fd.FdError) as e:
+                fd.fd_decode_paged(dec.h, q, pool, pool, table, bad_ps, sl, out, None, 1)
+            assert e.value.code == fd.FD_ERR_INVALID_ARG
+        with pytest.raises(fd.FdError) as e:                      # table rows too short for S_max
+            fd.fd_decode_paged(dec.h, q, pool, pool, table[:, :32].contiguous(), 16, sl, out, None, 1)
+        assert e.value.code == fd.FD_ERR_INVALID_ARG
+        with pytest.raises(fd.FdError) as e:
+            fd.fd_decode_paged(dec.h, q, pool, pool, None, 16, sl, out, None, 1)
+        assert e.value.code == fd.FD_ERR_INVALID_ARG
+        fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 1)
+        with pytest.raises(fd.FdError) as e:
+            fd.fd_decode_paged(dec.h, q, pool, pool, table, 16, sl, out, None, 1)
+        assert e.value.code == fd.FD_ERR_UNSUPPORTED
+        fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 0)
+        # out-of-range table entries are clamped into the pool: the call must complete
+        table.fill_(10 ** 6)
+        fd.fd_decode_paged(dec.h, q, pool, pool, table, 16, sl, out, None, 1)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out).all()
