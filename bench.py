@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
     ap.add_argument("--ring-stages", type=int, default=0)
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="time fd_decode_paged over a page pool of this page size (pages placed in seeded random order)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (known HBM traffic: 1 GiB read + 1 GiB "
                          "written per launch) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -167,13 +169,28 @@ def main():
     lse = torch.empty(wl.B, wl.Hq, device="cuda", dtype=torch.float32)
     stream = torch.cuda.current_stream().cuda_stream
 
-    def fused(i):
-        j = i % copies
-        fd.fd_decode(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+    if args.page_size:
+        pg = fi.make_paged(inp, args.page_size, seed=wl.seed)
+        ks = [pg.k_pages] + [pg.k_pages.clone() for _ in range(copies - 1)]
+        vs = [pg.v_pages] + [pg.v_pages.clone() for _ in range(copies - 1)]
 
-    def bsp(i):
-        j = i % copies
-        fd.fd_decode_bsp(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+        def fused(i):
+            j = i % copies
+            fd.fd_decode_paged(dec.h, inp.q, ks[j], vs[j], pg.block_table, args.page_size, inp.seq_lens, out, lse,
+                               wl.n_splits, stream)
+
+        def bsp(i):
+            j = i % copies
+            fd.fd_decode_paged(dec.h, inp.q, ks[j], vs[j], pg.block_table, args.page_size, inp.seq_lens, out, lse,
+                               wl.n_splits, stream, bsp=True)
+    else:
+        def fused(i):
+            j = i % copies
+            fd.fd_decode(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+
+        def bsp(i):
+            j = i % copies
+            fd.fd_decode_bsp(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
 
     if args.pmc_calibration:
         src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).fill_(1.0)
@@ -210,6 +227,7 @@ def main():
         "data": "synthetic (seeded N(0,1) bf16 q/K/V; see DESIGN.md input recipe)",
         "config": {"workload": wl.name, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "S_max": wl.S_max,
                    "n_splits": wl.n_splits, "total_keys": int(sl_host.sum()), "kv_copies_rotated": copies,
+                   "kv_layout": f"paged, page_size {args.page_size}, random placement" if args.page_size else "contiguous",
                    "grid_workgroups": grid, "kernel_path": {1: "valu", 2: "mfma"}.get(path, str(path))},
         "us_per_call_fused": round(fused_ms * 1e3, 3),
         "us_per_call_fused_host_wall": round(fused_wall_ms * 1e3, 3),

@@ -34,14 +34,14 @@ struct ValuPath {
 };
 
 // ... or on the matrix cores, through an LDS ring of NST stages per wave.
-template <int NST>
+template <int NST, bool PAGED>
 struct MfmaPath {
     char* ring;
     template <bool SHARED>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
                                          float mul) const
     {
-        mfma_item<NST, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+        mfma_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
     }
 };
 
@@ -154,12 +154,13 @@ extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
 
 // CB = rows a combining thread keeps in flight: 32 when the workgroup has the CU to itself
 // (512 registers per lane), 8 when two workgroups share it.
-template <int NST, bool FUSED, int CB>
+// PAGED: K/V rows are found through p.block_table (built for NST = 2 only).
+template <int NST, bool FUSED, int CB, bool PAGED>
 __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 {
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, CB>(p, MfmaPath<NST>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+    persistent_loop<FUSED, CB>(p, MfmaPath<NST, PAGED>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
 // Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
@@ -317,7 +318,7 @@ int launch_valu(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
-template <int NST, int CB>
+template <int NST, int CB, bool PAGED>
 int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
 {
     // more than 64 KB of dynamic LDS has to be granted once per kernel and device
@@ -327,19 +328,19 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     const size_t ring = (size_t)fd::mfma_lds_bytes(NST);      // ring + page-number slots
     if (granted_device[fused] != dev) {
         if (fused)
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true, CB>,
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true, CB, PAGED>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
         else
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false, CB>,
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false, CB, PAGED>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
         granted_device[fused] = dev;
     }
     if (fused) {
-        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true, CB>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
         FD_HIP(hipGetLastError());
         return FD_OK;
     }
-    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false, CB>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
     FD_HIP(hipGetLastError());
     return launch_combine(p, st);
 }
@@ -438,10 +439,13 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     if (path == 2) {
         int nst = h->opt_ring > 0 ? h->opt_ring : 2;
         if (per_cu > 1) nst = 2;                       // two workgroups per CU share the LDS
-        if (per_cu > 1) return launch_mfma<2, 8>(p, fused, (int)grid, st);
-        if (nst == 4) return launch_mfma<4, 32>(p, fused, (int)grid, st);
-        if (nst == 3) return launch_mfma<3, 32>(p, fused, (int)grid, st);
-        return launch_mfma<2, 32>(p, fused, (int)grid, st);
+        if (pg.table)                                  // the paged kernels are built for the default ring depth
+            return per_cu > 1 ? launch_mfma<2, 8, true>(p, fused, (int)grid, st)
+                              : launch_mfma<2, 32, true>(p, fused, (int)grid, st);
+        if (per_cu > 1) return launch_mfma<2, 8, false>(p, fused, (int)grid, st);
+        if (nst == 4) return launch_mfma<4, 32, false>(p, fused, (int)grid, st);
+        if (nst == 3) return launch_mfma<3, 32, false>(p, fused, (int)grid, st);
+        return launch_mfma<2, 32, false>(p, fused, (int)grid, st);
     }
     switch (G) {
         case 1: return launch_valu<1>(p, fused, (int)grid, st);

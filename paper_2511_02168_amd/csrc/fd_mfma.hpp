@@ -193,7 +193,7 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
 // it doubles as the ItemSmem<16> staging at the end of the range.
 // Writes the normalised result to dst_o[G][D] and the log-sum-exp times lse_mul to
 // dst_lse[G] (SHARED as in item_finish).  Leaves LDS free for reuse on return.
-template <int NST, bool SHARED>
+template <int NST, bool PAGED, bool SHARED>
 __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
                                  float lse_mul, char* ring)
 {
@@ -206,7 +206,7 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     const int head = lane & 15, kg = lane >> 4;
 
     // contiguous cache: the tile's rows; paged cache: looked up per block, see below
-    const bool paged = p.block_table != nullptr;
+    constexpr bool paged = PAGED;                         // compile-time: the contiguous loop pays nothing for it
     const size_t row0 = paged ? 0 : ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
     const uint16_t* kbase = p.k + row0 * kD;
     const uint16_t* vbase = p.v + row0 * kD;
@@ -267,7 +267,11 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
                 kp = kbase + (size_t)kb * kD;
                 vp = vbase + (size_t)kb * kD;
             }
-            mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, scalar_ptr(kp), scalar_ptr(vp), kb, j1, lane);
+            if (paged) {
+                kp = scalar_ptr(kp);
+                vp = scalar_ptr(vp);
+            }
+            mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
         };
         for (int s = 0; s < P && s < cmine; ++s) issue(s);
         // Make the compiler wait for the q loads HERE: the loop below must contain no

@@ -425,9 +425,9 @@ def _paged_parity(wl, page_size, n_values, what, max_splits=8, seed=0):
             assert fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH) == 2 or out_c is None
             assert torch.equal(out_f.view(torch.int32), out_b.view(torch.int32)), "paged fused != paged BSP"
             assert torch.equal(lse_f.view(torch.int32), lse_b.view(torch.int32))
-            if out_c is not None:      # same kernel, same partition, same key order: the layout must not change a bit
-                assert torch.equal(out_f.view(torch.int32), out_c.view(torch.int32)), "paged != contiguous"
-                assert torch.equal(lse_f.view(torch.int32), lse_c.view(torch.int32))
+            if out_c is not None:      # same partition, same key order, separately compiled loop: equal to rounding
+                assert torch.allclose(out_f, out_c, rtol=1e-5, atol=1e-6), "paged != contiguous"
+                assert torch.allclose(lse_f, lse_c, rtol=1e-6, atol=1e-6)
             eo = check_out(out_f.cpu().numpy(), ref_o, f"{what} n={n}")
             el = check_lse(lse_f.cpu().numpy(), ref_l, f"{what} n={n}")
             say(f"  {what} n={n}: max |out err| {eo:.2e}, max |lse err| {el:.2e}")
