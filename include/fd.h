@@ -157,8 +157,8 @@ int fd_decode_paged_bsp(fd_handle_t h, const void* q, const void* k_pages, const
 
 /*
  * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.
- *   FD_OPT_PATH          0 auto (MFMA kernel when Hq/Hkv >= 4, VALU kernel below),
- *                        1 force VALU (Hq/Hkv <= 8 only), 2 force MFMA
+ *   FD_OPT_PATH          0 auto (the MFMA kernel), 1 VALU kernel (Hq/Hkv <= 8 only),
+ *                        2 MFMA kernel
  *   FD_OPT_XCD_GROUPS    0 auto (8 when B*Hkv is a multiple of 8, except for at most 32
  *                        tiles with S_max > 16384; else 1), 1 = one global item list,
  *                        8 = items of a tile stay on one XCD (tile t -> workgroups with

@@ -375,10 +375,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         while ((1 << page_shift) < pg.page_size) ++page_shift;
     }
 
-    // which kernel: measured crossover on MI355X.  From 4 query heads per KV head on, the
-    // MFMA kernel wins (its K/V stream needs no registers, the VALU kernel's does and runs
-    // out of them as the per-head state grows); below, the matrix tile is mostly padding
-    // and the VALU kernel is as fast or faster.
+    // which kernel: the MFMA kernel by default for every group size.  Its K/V stream goes
+    // global -> LDS and needs no registers; measured on MI355X it is as fast as the VALU
+    // kernel or faster at every G (1 % slower on a 1K-key call, 2-20 % faster elsewhere,
+    // 5 % at G = 1 on 128K keys), although at G = 1 fifteen of its sixteen matrix rows are
+    // padding: the bound is HBM, not the matrix pipe.  The VALU kernel stays selectable.
     const int G = h->G;
     int path = h->opt_path;
     if (pg.table) {
@@ -386,7 +387,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         if (path == 1) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel does not read paged caches");
         path = 2;
     }
-    if (path == 0) path = G >= 4 ? 2 : 1;
+    if (path == 0) path = 2;
     if (path == 1 && G > 8) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for Hq/Hkv <= 8 (got %d)", G);
 
     // persistent grid: a fixed number of workgroups per CU, never more than there are items.

@@ -179,6 +179,33 @@ def test_every_group_size(G):
     full_parity(wl, inp, 0, max_splits=8, what=f"G={G} adaptive")
 
 
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_valu_kernel_every_group_size(G):
+    """The VALU kernel (FD_OPT_PATH = 1; no longer the default anywhere) on ragged lengths and edge sizes."""
+    wl = _generic(3, 2 * G, 2, 777, 220 + G, ragged=True)
+    say(f"case VALU kernel, G={G}, ragged S<=777 and S in 1, 33, 512")
+    inp = fi.make_inputs(wl, "cuda")
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=8) as dec:
+        fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 1)
+        for n in (4, 0):
+            fd.fd_debug_poison_workspace(dec.h)
+            out, lse = run_both(dec, inp, n)
+            assert fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH) == 1
+            check_out(out, ref_o, f"VALU G={G} n={n}")
+            check_lse(lse, ref_l, f"VALU G={G} n={n}")
+    for S in (1, 33, 512):
+        wl2 = _generic(2, 2 * G, 2, S, 230 + G + S)
+        inp2 = fi.make_inputs(wl2, "cuda")
+        ref_o, ref_l = oracle.decode(fi.bits(inp2.q), fi.bits(inp2.k), fi.bits(inp2.v), inp2.seq_lens.cpu().numpy())
+        with fd.FlashDecode(wl2.B, wl2.Hq, wl2.Hkv, wl2.S_max, max_splits=4) as dec:
+            fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 1)
+            for n in (1, 3):
+                out, lse = run_both(dec, inp2, n)
+                check_out(out, ref_o, f"VALU G={G} S={S} n={n}")
+                check_lse(lse, ref_l, f"VALU G={G} S={S} n={n}")
+
+
 @pytest.mark.parametrize("G,path,per_cu", [(1, 2, 1), (4, 2, 1), (4, 2, 2), (8, 1, 2), (8, 2, 1), (8, 2, 2), (16, 2, 2)])
 def test_both_kernels_on_the_same_shapes(G, path, per_cu):
     """FD_OPT_PATH forces the VALU (1) or MFMA (2) kernel; per_cu picks the MFMA ring depth."""
@@ -420,9 +447,9 @@ def _paged_parity(wl, page_size, n_values, what, max_splits=8, seed=0):
             out_f, lse_f = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, page_size, pg.seq_lens, n)
             out_b, lse_b = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, page_size, pg.seq_lens, n,
                                             bsp=True)
-            out_c, lse_c = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n) if wl.Hq // wl.Hkv >= 4 else (None, None)
+            out_c, lse_c = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n)
             torch.cuda.synchronize()
-            assert fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH) == 2 or out_c is None
+            assert fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH) == 2
             assert torch.equal(out_f.view(torch.int32), out_b.view(torch.int32)), "paged fused != paged BSP"
             assert torch.equal(lse_f.view(torch.int32), lse_b.view(torch.int32))
             if out_c is not None:      # same partition, same key order, separately compiled loop: equal to rounding
