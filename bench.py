@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
     ap.add_argument("--ring-stages", type=int, default=0)
+    ap.add_argument("--autotune", action="store_true",
+                    help="let fd_autotune pick the options for this shape first (untimed); the choice is reported")
     ap.add_argument("--page-size", type=int, default=0,
                     help="time fd_decode_paged over a page pool of this page size (pages placed in seeded random order)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -200,6 +202,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    tuned = None
+    if args.autotune and not args.page_size:
+        fd.fd_autotune(dec.h, inp.q, ks[0], vs[0], inp.seq_lens, out, lse, wl.n_splits, stream, reps=30)
+        tuned = {"path": fd.fd_get_option(dec.h, fd.FD_OPT_PATH), "xcd_groups": fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS),
+                 "wgs_per_cu": fd.fd_get_option(dec.h, fd.FD_OPT_WGS_PER_CU),
+                 "ring_stages": fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES)}
     fused_ms, fused_wall_ms = time_calls(fused, args.warmup, args.steps, torch)
     grid = fd.fd_get_option(dec.h, fd.FD_INFO_LAST_GRID)
     path = fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH)
@@ -228,7 +236,7 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "S_max": wl.S_max,
                    "n_splits": wl.n_splits, "total_keys": int(sl_host.sum()), "kv_copies_rotated": copies,
                    "kv_layout": f"paged, page_size {args.page_size}, random placement" if args.page_size else "contiguous",
-                   "grid_workgroups": grid, "kernel_path": {1: "valu", 2: "mfma"}.get(path, str(path))},
+                   "autotuned_options": tuned, "grid_workgroups": grid, "kernel_path": {1: "valu", 2: "mfma"}.get(path, str(path))},
         "us_per_call_fused": round(fused_ms * 1e3, 3),
         "us_per_call_fused_host_wall": round(fused_wall_ms * 1e3, 3),
         "us_per_call_bsp": None if bsp_ms is None else round(bsp_ms * 1e3, 3),

@@ -156,6 +156,23 @@ int fd_decode_paged_bsp(fd_handle_t h, const void* q, const void* k_pages, const
                         void* stream);
 
 /*
+ * Picks the handle's options by measurement: SYNCHRONOUS, unlike every other call here.
+ * Runs fd_decode on the given arguments (3 untimed + `reps` timed calls, HIP events on
+ * `stream`) for every combination of FD_OPT_XCD_GROUPS {1, 8 where allowed} with
+ * (FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES) in {(1,2), (1,3), (1,4), (2,2)} of the MFMA
+ * kernel, plus the VALU kernel where Hq/Hkv <= 8, and leaves the handle set to the
+ * fastest (read the choice back with fd_get_option); *best_us (host, may be NULL) receives
+ * its mean time per call in microseconds.  out / lse hold a valid result afterwards.  On
+ * error the options are left as they were.  The defaults are rules fitted to measurements
+ * on a few shapes; this call replaces the rule by the measurement for the shape and the
+ * data placement at hand (the rules miss by up to 10 % on shapes between their samples).
+ * Results of later calls differ from the defaults' only in rounding (another partition).
+ */
+int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
+                const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream,
+                int32_t reps, float* best_us);
+
+/*
  * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.
  *   FD_OPT_PATH          0 auto (the MFMA kernel), 1 VALU kernel (Hq/Hkv <= 8 only),
  *                        2 MFMA kernel

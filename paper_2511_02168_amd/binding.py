@@ -20,7 +20,7 @@ FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES = 1, 2, 3,
 FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH = 100, 101, 102
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
-           "fd_decode_paged", "fd_decode_paged_bsp", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
+           "fd_decode_paged", "fd_decode_paged_bsp", "fd_autotune", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
            "fd_debug_set_trace", "fd_debug_stream_read",
            "fd_last_error", "fd_version"]
 
@@ -75,6 +75,8 @@ def lib():
             fn = getattr(L, name)
             fn.restype = ctypes.c_int
             fn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, i32, vp]
+        L.fd_autotune.restype = ctypes.c_int
+        L.fd_autotune.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.fd_debug_stream_read.restype = ctypes.c_int
         L.fd_debug_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.fd_last_error.restype = ctypes.c_char_p
@@ -120,6 +122,14 @@ def fd_decode_paged(h, q, k_pages, v_pages, block_table, page_size: int, seq_len
               0 if block_table is None else int(block_table.shape[1]), int(k_pages.shape[0]), _ptr(seq_lens),
               _ptr(out), _ptr(lse),
               int(n_splits), ctypes.c_void_p(stream)))
+
+
+def fd_autotune(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0, reps: int = 20) -> float:
+    """Synchronous: measures the option combinations and keeps the fastest; returns its us per call."""
+    best = ctypes.c_float(0.0)
+    _check(lib().fd_autotune(h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out), _ptr(lse),
+                             int(n_splits), ctypes.c_void_p(stream), int(reps), ctypes.byref(best)))
+    return float(best.value)
 
 
 def fd_reset(h, stream: int = 0) -> None:

@@ -544,6 +544,65 @@ int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void*
     return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, false);
 }
 
+int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                float* out, float* lse, int32_t n_splits, void* stream, int32_t reps, float* best_us)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (reps <= 0 || reps > 10000) return fail(FD_ERR_INVALID_ARG, "reps must be in 1..10000");
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    FD_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(FD_ERR_HIP, "hipEventCreate failed");
+    }
+    const int tiles = h->cfg.B * h->cfg.Hkv;
+    // candidates: {work lists} x {(workgroups per CU, ring stages)}, MFMA kernel; plus the VALU kernel where it is built
+    struct Cand { int path, xcd, per_cu, ring; };
+    Cand cands[16];
+    int n_cand = 0;
+    const int xcds[2] = {1, 8};
+    const int shapes[4][2] = {{1, 2}, {1, 3}, {1, 4}, {2, 2}};
+    for (int xi = 0; xi < 2; ++xi) {
+        if (xcds[xi] == 8 && tiles % 8 != 0) continue;
+        for (int si = 0; si < 4; ++si) cands[n_cand++] = Cand{2, xcds[xi], shapes[si][0], shapes[si][1]};
+        if (h->G <= 8) cands[n_cand++] = Cand{1, xcds[xi], 0, 0};
+    }
+    const Cand saved = {h->opt_path, h->opt_xcd, h->opt_wgs_per_cu, h->opt_ring};
+    float best = 0.f;
+    int best_i = -1;
+    rc = FD_OK;
+    for (int i = 0; i < n_cand && rc == FD_OK; ++i) {
+        h->opt_path = cands[i].path; h->opt_xcd = cands[i].xcd; h->opt_wgs_per_cu = cands[i].per_cu; h->opt_ring = cands[i].ring;
+        for (int w = 0; w < 3 && rc == FD_OK; ++w)
+            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, true);
+        if (rc != FD_OK) break;
+        if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(FD_ERR_HIP, "hipEventRecord failed"); break; }
+        for (int r = 0; r < reps && rc == FD_OK; ++r)
+            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, true);
+        if (rc != FD_OK) break;
+        float ms = 0.f;
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+            rc = fail(FD_ERR_HIP, "timing a candidate failed");
+            break;
+        }
+        const float us = ms * 1000.f / (float)reps;
+        if (best_i < 0 || us < best) { best = us; best_i = i; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != FD_OK || best_i < 0) {
+        h->opt_path = saved.path; h->opt_xcd = saved.xcd; h->opt_wgs_per_cu = saved.per_cu; h->opt_ring = saved.ring;
+        return rc != FD_OK ? rc : fail(FD_ERR_HIP, "no candidate could be timed");
+    }
+    h->opt_path = cands[best_i].path; h->opt_xcd = cands[best_i].xcd; h->opt_wgs_per_cu = cands[best_i].per_cu;
+    h->opt_ring = cands[best_i].ring;
+    if (best_us) *best_us = best;
+    return FD_OK;
+}
+
 int fd_decode_paged(fd_handle_t h, const void* q, const void* k_pages, const void* v_pages, const int32_t* block_table,
                     int32_t page_size, int32_t pages_per_seq, int32_t num_pages, const int32_t* seq_lens, float* out,
                     float* lse, int32_t n_splits, void* stream)

@@ -527,3 +527,27 @@ def test_paged_argument_errors():
         fd.fd_decode_paged(dec.h, q, pool, pool, table, 16, sl, out, None, 1)
         torch.cuda.synchronize()
         assert torch.isfinite(out).all()
+
+
+def test_autotune_leaves_valid_options_and_results():
+    say("case fd_autotune on two shapes")
+    for wl in (_generic(4, 16, 2, 3000, 800, ragged=True), _generic(2, 12, 3, 900, 801)):
+        inp = fi.make_inputs(wl, "cuda")
+        ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+        with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=8) as dec:
+            out = torch.empty(wl.B, wl.Hq, 128, device="cuda")
+            lse = torch.empty(wl.B, wl.Hq, device="cuda")
+            us = fd.fd_autotune(dec.h, inp.q, inp.k, inp.v, inp.seq_lens, out, lse, 0, reps=5)
+            assert us > 0
+            assert fd.fd_get_option(dec.h, fd.FD_OPT_PATH) in (1, 2)
+            assert fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS) in (1, 8)
+            say(f"  chose path {fd.fd_get_option(dec.h, fd.FD_OPT_PATH)} lists {fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS)} "
+                f"per CU {fd.fd_get_option(dec.h, fd.FD_OPT_WGS_PER_CU)} ring {fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES)}: {us:.1f} us")
+            check_out(out.cpu().numpy(), ref_o, "autotune result")        # the last timed call's result is valid
+            check_lse(lse.cpu().numpy(), ref_l, "autotune result")
+            out2, lse2 = run_both(dec, inp, 0)
+            check_out(out2, ref_o, "after autotune")
+            check_lse(lse2, ref_l, "after autotune")
+            with pytest.raises(fd.FdError) as e:
+                fd.fd_autotune(dec.h, inp.q, inp.k, inp.v, inp.seq_lens, out, lse, 0, reps=0)
+            assert e.value.code == fd.FD_ERR_INVALID_ARG
