@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="rotating K/V copies (0 = enough to exceed 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bsp", action="store_true")
+    ap.add_argument("--no-waits", action="store_true", help="skip the fine-grained-waits variant (fd_decode_waits)")
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only streaming kernel (achievable bandwidth)")
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
@@ -215,6 +216,14 @@ def main():
     if not args.no_bsp:
         bsp_ms, _ = time_calls(bsp, args.warmup, args.steps, torch)
 
+    waits_ms = None
+    if not args.no_waits and not args.page_size and path == 2:
+        def waits(i):
+            j = i % copies
+            fd.fd_decode_waits(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+        waits_ms, _ = time_calls(waits, args.warmup, args.steps, torch)
+        if fd.fd_get_option(dec.h, fd.FD_INFO_WAIT_GAVE_UP):
+            waits_ms = None
     pct_fused = per_call_percentiles(fused, min(args.steps, 200), torch)
     pct_bsp = None if args.no_bsp else per_call_percentiles(bsp, min(args.steps, 200), torch)
     probe_gbs = None if args.no_probe else streaming_probe(fd, torch, stream)
@@ -240,6 +249,7 @@ def main():
         "us_per_call_fused": round(fused_ms * 1e3, 3),
         "us_per_call_fused_host_wall": round(fused_wall_ms * 1e3, 3),
         "us_per_call_bsp": None if bsp_ms is None else round(bsp_ms * 1e3, 3),
+        "us_per_call_fine_grained_waits": None if waits_ms is None else round(waits_ms * 1e3, 3),
         "fused_over_bsp": None if bsp_ms is None else round(fused_ms / bsp_ms, 4),
         "us_single_call_fused_p10_p50_p90": pct_fused,
         "us_single_call_bsp_p10_p50_p90": pct_bsp,

@@ -80,8 +80,9 @@ size_t fd_workspace_bytes(const fd_config* cfg);
 
 /*
  * Validates cfg, allocates the workspace on the current HIP device (partials
- * [B,Hkv,max_splits,G,D] fp32, their LSEs, one arrival counter per tile) and
- * zeroes the counters.  Synchronous.  *out receives the handle.
+ * [B,Hkv,max_splits,G,D] fp32, their LSEs, one arrival counter per tile), zeroes
+ * the counters, and creates the stream and two events fd_decode_waits uses.
+ * Synchronous.  *out receives the handle.
  */
 int fd_create(const fd_config* cfg, fd_handle_t* out);
 
@@ -126,6 +127,21 @@ int fd_decode(fd_handle_t h, const void* q, const void* k_cache, const void* v_c
 int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
                   const int32_t* seq_lens, float* out, float* lse, int32_t n_splits,
                   void* stream);
+
+/*
+ * Fine-grained waits (Section 4.2.4), the paper's step between the bulk-synchronous baseline
+ * and the fused kernel: same arguments and results (bitwise) as fd_decode.  Two kernels run
+ * SIDE BY SIDE: kernel 1 (on `stream`) writes partials and bumps a tile's arrival counter;
+ * the combine kernel (on a second stream the handle owns, forked from and joined to `stream`
+ * with events, so that `stream` sees one operation) waits per tile until the counter is
+ * complete, then merges that tile, while other tiles are still being attended.  Kernel 1
+ * never waits, so the counts always complete; the combine kernel's wait is bounded all the
+ * same (FD_OPT_SPIN_LIMIT polls, ~0.2 us each): if it ever gives up, FD_INFO_WAIT_GAVE_UP
+ * reads 1, out / lse of that call are undefined, and fd_reset is needed before the next
+ * call.  MFMA kernel, contiguous cache only (else FD_ERR_UNSUPPORTED).
+ */
+int fd_decode_waits(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
+                    const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream);
 
 /*
  * The same computation over a PAGED KV cache (the layout decode servers use).
@@ -183,16 +199,19 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
  *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto)
  *   FD_OPT_RING_STAGES   MFMA kernel: stages (16 keys of K and V, 8 KB) in each wave's
  *                        LDS ring: 0 auto (2), 2, 3 or 4; with 2 workgroups per CU always 2
- *   FD_INFO_*            read-only, through fd_get_option
+ *   FD_OPT_SPIN_LIMIT    fd_decode_waits: polls before a waiting workgroup gives up (0 = 4194304)
+ *   FD_INFO_*            read-only, through fd_get_option; FD_INFO_WAIT_GAVE_UP synchronises the device
  */
 enum {
     FD_OPT_PATH = 1,
     FD_OPT_XCD_GROUPS = 2,
     FD_OPT_WGS_PER_CU = 3,
     FD_OPT_RING_STAGES = 4,
+    FD_OPT_SPIN_LIMIT = 5,
     FD_INFO_NUM_CUS = 100,
     FD_INFO_LAST_GRID = 101,   /* workgroups of the last fused / split launch */
-    FD_INFO_LAST_PATH = 102    /* 1 VALU, 2 MFMA */
+    FD_INFO_LAST_PATH = 102,   /* 1 VALU, 2 MFMA */
+    FD_INFO_WAIT_GAVE_UP = 103 /* 1 after a fd_decode_waits call whose combine kernel gave up waiting */
 };
 int fd_set_option(fd_handle_t h, int32_t key, int32_t value);
 int fd_get_option(fd_handle_t h, int32_t key, int32_t* value);

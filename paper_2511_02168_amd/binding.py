@@ -16,11 +16,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfd.so")
 
 FD_OK, FD_ERR_INVALID_ARG, FD_ERR_UNSUPPORTED, FD_ERR_WORKSPACE, FD_ERR_HIP = 0, -1, -2, -3, -4
-FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES = 1, 2, 3, 4
-FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH = 100, 101, 102
+FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES, FD_OPT_SPIN_LIMIT = 1, 2, 3, 4, 5
+FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH, FD_INFO_WAIT_GAVE_UP = 100, 101, 102, 103
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
-           "fd_decode_paged", "fd_decode_paged_bsp", "fd_autotune", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
+           "fd_decode_paged", "fd_decode_paged_bsp", "fd_decode_waits", "fd_autotune", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
            "fd_debug_set_trace", "fd_debug_stream_read",
            "fd_last_error", "fd_version"]
 
@@ -58,7 +58,7 @@ def lib():
         L.fd_destroy.argtypes = [vp]
         L.fd_reset.restype = ctypes.c_int
         L.fd_reset.argtypes = [vp, vp]
-        for fn in (L.fd_decode, L.fd_decode_bsp):
+        for fn in (L.fd_decode, L.fd_decode_bsp, L.fd_decode_waits):
             fn.restype = ctypes.c_int
             fn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.fd_set_option.restype = ctypes.c_int
@@ -145,6 +145,11 @@ def fd_decode(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream:
                            int(n_splits), ctypes.c_void_p(stream)))
 
 
+def fd_decode_waits(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:
+    _check(lib().fd_decode_waits(h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out), _ptr(lse),
+                                 int(n_splits), ctypes.c_void_p(stream)))
+
+
 def fd_decode_bsp(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:
     _check(lib().fd_decode_bsp(h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out), _ptr(lse),
                                int(n_splits), ctypes.c_void_p(stream)))
@@ -221,7 +226,7 @@ class FlashDecode:
             assert lse.is_cuda and lse.dtype == torch.float32 and tuple(lse.shape) == (c.B, c.Hq) and lse.is_contiguous()
 
     def decode(self, q, k, v, seq_lens, n_splits: int, out=None, lse=None, bsp: bool = False,
-               stream: Optional[int] = None, want_lse: bool = True):
+               stream: Optional[int] = None, want_lse: bool = True, waits: bool = False):
         import torch
         c = self.cfg
         if out is None:
@@ -231,7 +236,7 @@ class FlashDecode:
         self._check_tensors(q, k, v, seq_lens, out, lse)
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
-        fn = fd_decode_bsp if bsp else fd_decode
+        fn = fd_decode_waits if waits else fd_decode_bsp if bsp else fd_decode
         fn(self.h, q, k, v, seq_lens, out, lse, n_splits, stream)
         return out, lse
 

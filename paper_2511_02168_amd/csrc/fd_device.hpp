@@ -39,6 +39,8 @@ struct Params {
     float* part_o;            // [B*Hkv, max_splits, G, D]
     float* part_lse;          // [B*Hkv, max_splits, G]   (log2 units)
     uint32_t* counters;       // [B*Hkv]
+    uint32_t* status;         // [1] set non-zero by a waiting combine kernel that gave up
+    uint32_t spin_limit;      // polls a waiting combine workgroup makes before it gives up
     int32_t B, Hq, Hkv, G, S_max;
     int32_t n_splits;         // 0 = adaptive
     int32_t max_splits;

@@ -51,11 +51,18 @@ struct SchedSmem {
     int is_last;
 };
 
+// What a workgroup does after a partial: nothing (kernel 1 of the bulk-synchronous
+// baseline), count and combine if last (the fused kernel), or count only (kernel 1 of the
+// fine-grained-waits variant, whose combine kernel waits for the counts).
+constexpr int kModeBsp = 0, kModeFused = 1, kModeSignal = 2;
+// Counter value of a tile whose result kernel 1 wrote itself (fine-grained waits).
+constexpr uint32_t kTileDirect = 0x80000000u;
+
 // The persistent loop of a workgroup.  FUSED: steps a1-a8 in one launch (the
 // workgroup that completes a tile's split count merges the tile: paper Section
 // 4.2.5 / Algorithm 4 without the barrier and without the second launch).
 // !FUSED: steps a1-a6 only (kernel 1 of the bulk-synchronous baseline, Section 4.2.2).
-template <bool FUSED, int COMB_BATCH, class Path>
+template <int MODE, int COMB_BATCH, class Path>
 __device__ __forceinline__ void persistent_loop(const Params& p, const Path& path, SchedSmem& ss, CombineSmem& comb)
 {
     const int G = p.G;
@@ -93,7 +100,13 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
                 if (l && threadIdx.x < G) l[threadIdx.x] = -INFINITY;
             }
             // bulk-synchronous mode: tell kernel 2 that this tile needs no combine
-            if (!FUSED && threadIdx.x == 0) p.counters[it.tile] = 1u;
+            if (MODE == kModeBsp && threadIdx.x == 0) p.counters[it.tile] = 1u;
+            // fine-grained waits: tell the waiting combine workgroup that there is nothing to merge
+            if (MODE == kModeSignal) {
+                __syncthreads();
+                if (threadIdx.x == 0)
+                    __hip_atomic_store(&p.counters[it.tile], kTileDirect, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             continue;
         }
 
@@ -108,7 +121,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
         }
 
         trace_event(p, kEvPartialOut);
-        if (FUSED) {
+        if (MODE != kModeBsp) {
             // a7: the partial went out with coherent stores; once they are acknowledged
             // and every wave has reached the barrier, one thread counts the run's splits
             // as arrived (Algorithm 4: push, then atomic increment of the flag).
@@ -123,7 +136,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             }
             __syncthreads();
             trace_event(p, kEvCounted);
-            if (ss.is_last) {
+            if (MODE == kModeFused && ss.is_last) {
                 const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
                 combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, &sch);
                 if (threadIdx.x == 0)                               // re-arm for the next call
@@ -147,7 +160,7 @@ __global__ __launch_bounds__(kWgThreads, (G <= 3 ? 2 : 1)) void fd_valu_kernel(P
 {
     __shared__ ValuWgSmem<G> sm;
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, (G <= 2 ? 16 : 8)>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
+    persistent_loop<(FUSED ? kModeFused : kModeBsp), (G <= 2 ? 16 : 8)>(p, ValuPath<G>{&sm.item}, ss, sm.comb);
 }
 
 extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
@@ -160,7 +173,15 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 {
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
-    persistent_loop<FUSED, CB>(p, MfmaPath<NST, PAGED>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, MfmaPath<NST, PAGED>{fd_dyn_smem}, ss,
+                                                        *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+}
+
+// Kernel 1 of the fine-grained-waits variant (Section 4.2.4): partials and arrival counts, no combine.
+__global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_signal_kernel(Params p)
+{
+    __shared__ SchedSmem ss;
+    persistent_loop<kModeSignal, 8>(p, MfmaPath<2, false>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
 // Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
@@ -183,6 +204,44 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
     trace_event(p, kEvEnd);
 }
 
+
+// Kernel 2 of the fine-grained-waits variant (Section 4.2.4; Algorithm 4 Part 2 as the paper
+// writes it: the consumer waits on the tile's flag, then combines).  Launched on a second
+// stream next to kernel 1.  A workgroup takes tiles blockIdx.x, + gridDim.x, ...; thread 0
+// polls the tile's arrival counter with coherent loads until the count is complete, the
+// other waves sleep at the barrier.  Kernel 1 never waits for anything, so the counts always
+// complete; the poll is bounded all the same (p.spin_limit): a workgroup that gives up sets
+// *p.status and leaves its remaining tiles alone.  Capped at 128 registers so that it fits
+// beside a workgroup of kernel 1 on every SIMD.
+__global__ __launch_bounds__(kWgThreads, 4) void fd_combine_wait_kernel(Params p)
+{
+    __shared__ CombineSmem sm;
+    __shared__ uint32_t seen;
+    const int tiles = p.B * p.Hkv;
+    for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const int b = tile / p.Hkv, kvh = tile - b * p.Hkv;
+        const uint32_t n = (uint32_t)num_splits_of(p, seq_len_of(p, b));
+        if (threadIdx.x == 0) {
+            uint32_t c = 0, polls = 0;
+            while (true) {
+                c = __hip_atomic_load(&p.counters[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (c >= n || ++polls >= p.spin_limit) break;
+                __builtin_amdgcn_s_sleep(32);       // ~1 us between polls: hundreds of pollers must not load the memory system
+            }
+            seen = c;
+        }
+        __syncthreads();
+        const uint32_t c = seen;
+        __syncthreads();
+        if (c < n) {                       // gave up: report, touch nothing else
+            if (threadIdx.x == 0) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        if (c != kTileDirect) combine_tile<8>(p, tile, b, kvh, (int)n, sm);
+        if (threadIdx.x == 0)              // re-arm for the next call
+            __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 
 // Measurement aid: reads `n_vec` 16-byte vectors once with the loads the K/V stream uses
 // (128-bit, non-temporal), one contiguous block per workgroup, and folds them into a
@@ -241,7 +300,7 @@ int fail(int code, const char* fmt, ...)
 constexpr uint32_t kMagic = 0x46444831u;
 
 struct Layout {
-    size_t part_o_off, part_lse_off, counters_off, total;
+    size_t part_o_off, part_lse_off, counters_off, status_off, total;
 };
 
 }  // namespace
@@ -254,7 +313,9 @@ struct fd_handle_s {
     int num_cus;
     void* workspace;
     Layout lay;
-    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring;
+    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring, opt_spin_limit;
+    hipStream_t side_stream;      // fine-grained waits: the waiting combine kernel runs here
+    hipEvent_t ev_fork, ev_join;
     int last_grid, last_path;
     unsigned long long* trace;
     int trace_capacity;      // workgroups the trace buffer has room for
@@ -288,8 +349,18 @@ Layout make_layout(const fd_config& c)
     l.part_o_off = 0;
     l.part_lse_off = up(tiles * c.max_splits * G * fd::kD * sizeof(float));
     l.counters_off = l.part_lse_off + up(tiles * c.max_splits * G * sizeof(float));
-    l.total = l.counters_off + up(tiles * sizeof(uint32_t));
+    l.status_off = l.counters_off + up(tiles * sizeof(uint32_t));
+    l.total = l.status_off + 256;
     return l;
+}
+
+void release_sync_objects(fd_handle_t h)
+{
+    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+    if (h->side_stream) (void)hipStreamDestroy(h->side_stream);
+    h->ev_fork = h->ev_join = nullptr;
+    h->side_stream = nullptr;
 }
 
 int check_handle(fd_handle_t h)
@@ -345,6 +416,34 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
+// Fine-grained waits (Section 4.2.4): kernel 1 (partials + arrival counts) on the caller's
+// stream, the waiting combine kernel on the handle's second stream, forked and joined with
+// events so that the caller's stream sees one operation.  Kernel 1 goes first: if the
+// hardware ever ran the two one after the other, the combine kernel would find every count
+// complete instead of waiting for a kernel that cannot start.
+int launch_waits(fd_handle_t h, const fd::Params& p, int grid, hipStream_t st)
+{
+    static thread_local int granted_device = -1;
+    int dev = 0;
+    FD_HIP(hipGetDevice(&dev));
+    const size_t lds = (size_t)fd::mfma_lds_bytes(2);
+    if (granted_device != dev) {
+        FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_signal_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        granted_device = dev;
+    }
+    const int tiles = p.B * p.Hkv;
+    const int waiters = tiles < h->num_cus ? tiles : h->num_cus;
+    FD_HIP(hipEventRecord(h->ev_fork, st));
+    FD_HIP(hipStreamWaitEvent(h->side_stream, h->ev_fork, 0));
+    hipLaunchKernelGGL(fd::fd_mfma_signal_kernel, dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+    FD_HIP(hipGetLastError());
+    hipLaunchKernelGGL(fd::fd_combine_wait_kernel, dim3(waiters), dim3(fd::kWgThreads), 0, h->side_stream, p);
+    FD_HIP(hipGetLastError());
+    FD_HIP(hipEventRecord(h->ev_join, h->side_stream));
+    FD_HIP(hipStreamWaitEvent(st, h->ev_join, 0));
+    return FD_OK;
+}
+
 // Paged-cache arguments of a call; table == nullptr for the contiguous layout.
 struct PagedArgs {
     const int32_t* table;
@@ -352,8 +451,9 @@ struct PagedArgs {
 };
 
 int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, const int32_t* seq_lens, float* out,
-                  float* lse, int32_t n_splits, void* stream, bool fused, const PagedArgs& pg = PagedArgs{nullptr, 0, 0, 0})
+                  float* lse, int32_t n_splits, void* stream, int mode, const PagedArgs& pg = PagedArgs{nullptr, 0, 0, 0})
 {
+    const bool fused = mode == fd::kModeFused;
     int rc = check_handle(h);
     if (rc) return rc;
     if (!q || !k || !v || !seq_lens || !out) return fail(FD_ERR_INVALID_ARG, "q, k_cache, v_cache, seq_lens, out must be non-NULL");
@@ -388,6 +488,10 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         path = 2;
     }
     if (path == 0) path = 2;
+    if (mode == fd::kModeSignal) {
+        if (path != 2 || pg.table) return fail(FD_ERR_UNSUPPORTED, "the fine-grained-waits variant exists for the MFMA kernel on a contiguous cache only");
+        if (!h->side_stream) return fail(FD_ERR_HIP, "the handle has no second stream");
+    }
     if (path == 1 && G > 8) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for Hq/Hkv <= 8 (got %d)", G);
 
     // persistent grid: a fixed number of workgroups per CU, never more than there are items.
@@ -396,6 +500,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     // the queues in front of memory, which every dependent access of the tail then waits in.
     const long long items_max = (long long)tiles * (n_splits > 0 ? n_splits : c.max_splits);
     int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : ((path == 2 || G >= 4) ? 1 : 2);
+    if (mode == fd::kModeSignal) per_cu = 1;
     if (path == 2 && per_cu > 2) per_cu = 2;
     long long grid = (long long)h->num_cus * per_cu;
     if (grid > items_max) grid = items_max;
@@ -426,6 +531,8 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.part_o = (float*)(ws + h->lay.part_o_off);
     p.part_lse = (float*)(ws + h->lay.part_lse_off);
     p.counters = (uint32_t*)(ws + h->lay.counters_off);
+    p.status = (uint32_t*)(ws + h->lay.status_off);
+    p.spin_limit = h->opt_spin_limit > 0 ? (uint32_t)h->opt_spin_limit : (1u << 22);
     p.B = c.B; p.Hq = c.Hq; p.Hkv = c.Hkv; p.G = h->G; p.S_max = c.S_max;
     p.n_splits = n_splits;
     p.max_splits = c.max_splits;
@@ -437,6 +544,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     hipStream_t st = (hipStream_t)stream;
     h->last_grid = (int)grid;
     h->last_path = path;
+    if (mode == fd::kModeSignal) return launch_waits(h, p, (int)grid, st);
     if (path == 2) {
         int nst = h->opt_ring > 0 ? h->opt_ring : 2;
         if (per_cu > 1) nst = 2;                       // two workgroups per CU share the LDS
@@ -491,13 +599,24 @@ int fd_create(const fd_config* cfg, fd_handle_t* out)
     h->device = dev;
     h->num_cus = prop.multiProcessorCount;
     h->lay = make_layout(*cfg);
-    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = 0;
+    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = h->opt_spin_limit = 0;
+    h->side_stream = nullptr;
+    h->ev_fork = h->ev_join = nullptr;
     h->last_grid = h->last_path = 0;
     h->trace = nullptr;
     h->trace_capacity = 0;
+    // second stream (default priority) and fork/join events for the fine-grained-waits variant
+    if (hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming) != hipSuccess) {
+        release_sync_objects(h);
+        delete h;
+        return fail(FD_ERR_HIP, "creating the handle's stream and events failed");
+    }
     hipError_t e = hipMalloc(&h->workspace, h->lay.total);
     if (e != hipSuccess) {
         const size_t want = h->lay.total;
+        release_sync_objects(h);
         delete h;
         return fail(FD_ERR_WORKSPACE, "hipMalloc of %zu workspace bytes failed: %s", want, hipGetErrorString(e));
     }
@@ -518,6 +637,7 @@ int fd_destroy(fd_handle_t h)
     if (rc) return rc;
     h->magic = 0;
     hipError_t e = hipFree(h->workspace);
+    release_sync_objects(h);
     delete h;
     if (e != hipSuccess) return fail(FD_ERR_HIP, "hipFree: %s", hipGetErrorString(e));
     return FD_OK;
@@ -535,13 +655,19 @@ int fd_reset(fd_handle_t h, void* stream)
 int fd_decode(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
               float* out, float* lse, int32_t n_splits, void* stream)
 {
-    return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, true);
+    return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
 }
 
 int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
                   float* out, float* lse, int32_t n_splits, void* stream)
 {
-    return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, false);
+    return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeBsp);
+}
+
+int fd_decode_waits(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                    float* out, float* lse, int32_t n_splits, void* stream)
+{
+    return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeSignal);
 }
 
 int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
@@ -576,11 +702,11 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
     for (int i = 0; i < n_cand && rc == FD_OK; ++i) {
         h->opt_path = cands[i].path; h->opt_xcd = cands[i].xcd; h->opt_wgs_per_cu = cands[i].per_cu; h->opt_ring = cands[i].ring;
         for (int w = 0; w < 3 && rc == FD_OK; ++w)
-            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, true);
+            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
         if (rc != FD_OK) break;
         if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(FD_ERR_HIP, "hipEventRecord failed"); break; }
         for (int r = 0; r < reps && rc == FD_OK; ++r)
-            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, true);
+            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
         if (rc != FD_OK) break;
         float ms = 0.f;
         if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
@@ -608,7 +734,7 @@ int fd_decode_paged(fd_handle_t h, const void* q, const void* k_pages, const voi
                     float* lse, int32_t n_splits, void* stream)
 {
     if (!block_table) return fail(FD_ERR_INVALID_ARG, "block_table must be non-NULL");
-    return decode_common(h, q, k_pages, v_pages, seq_lens, out, lse, n_splits, stream, true,
+    return decode_common(h, q, k_pages, v_pages, seq_lens, out, lse, n_splits, stream, fd::kModeFused,
                          PagedArgs{block_table, page_size, pages_per_seq, num_pages});
 }
 
@@ -617,7 +743,7 @@ int fd_decode_paged_bsp(fd_handle_t h, const void* q, const void* k_pages, const
                         const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream)
 {
     if (!block_table) return fail(FD_ERR_INVALID_ARG, "block_table must be non-NULL");
-    return decode_common(h, q, k_pages, v_pages, seq_lens, out, lse, n_splits, stream, false,
+    return decode_common(h, q, k_pages, v_pages, seq_lens, out, lse, n_splits, stream, fd::kModeBsp,
                          PagedArgs{block_table, page_size, pages_per_seq, num_pages});
 }
 
@@ -638,6 +764,10 @@ int fd_set_option(fd_handle_t h, int32_t key, int32_t value)
             if (value < 0 || value > 16) return fail(FD_ERR_INVALID_ARG, "FD_OPT_WGS_PER_CU must be in 0..16");
             h->opt_wgs_per_cu = value;
             return FD_OK;
+        case FD_OPT_SPIN_LIMIT:
+            if (value < 0) return fail(FD_ERR_INVALID_ARG, "FD_OPT_SPIN_LIMIT must be >= 0");
+            h->opt_spin_limit = value;
+            return FD_OK;
         case FD_OPT_RING_STAGES:
             if (value != 0 && (value < 2 || value > 4)) return fail(FD_ERR_INVALID_ARG, "FD_OPT_RING_STAGES must be 0, 2, 3 or 4");
             h->opt_ring = value;
@@ -657,6 +787,14 @@ int fd_get_option(fd_handle_t h, int32_t key, int32_t* value)
         case FD_OPT_XCD_GROUPS: *value = h->opt_xcd; return FD_OK;
         case FD_OPT_WGS_PER_CU: *value = h->opt_wgs_per_cu; return FD_OK;
         case FD_OPT_RING_STAGES: *value = h->opt_ring; return FD_OK;
+        case FD_OPT_SPIN_LIMIT: *value = h->opt_spin_limit; return FD_OK;
+        case FD_INFO_WAIT_GAVE_UP: {
+            uint32_t flag = 0;
+            FD_HIP(hipDeviceSynchronize());
+            FD_HIP(hipMemcpy(&flag, (char*)h->workspace + h->lay.status_off, sizeof(flag), hipMemcpyDeviceToHost));
+            *value = (int32_t)flag;
+            return FD_OK;
+        }
         case FD_INFO_NUM_CUS: *value = h->num_cus; return FD_OK;
         case FD_INFO_LAST_GRID: *value = h->last_grid; return FD_OK;
         case FD_INFO_LAST_PATH: *value = h->last_path; return FD_OK;

@@ -551,3 +551,61 @@ def test_autotune_leaves_valid_options_and_results():
             with pytest.raises(fd.FdError) as e:
                 fd.fd_autotune(dec.h, inp.q, inp.k, inp.v, inp.seq_lens, out, lse, 0, reps=0)
             assert e.value.code == fd.FD_ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------- fine-grained waits
+
+@pytest.mark.parametrize("shape", [(2, 16, 2, 3000, 8), (8, 8, 8, 1024, 4), (1, 8, 1, 40000, 64), (3, 12, 3, 700, 0),
+                                   (40, 16, 8, 600, 0)])
+def test_fine_grained_waits_equal_the_fused_result(shape):
+    """fd_decode_waits: kernel 1 and a waiting combine kernel side by side on two streams.
+    Same partition and same combine order as the fused kernel: bitwise equal.  Calls are
+    repeated back to back and interleaved with fused calls (shared counters must re-arm)."""
+    B, Hq, Hkv, S, n = shape
+    wl = _generic(B, Hq, Hkv, S, 900 + B + S, ragged=(n == 0))
+    say(f"case fine-grained waits B{B} Hq{Hq} Hkv{Hkv} S{S} n{n}")
+    inp = fi.make_inputs(wl, "cuda")
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max(n, 1) if n else 8) as dec:
+        fd.fd_debug_poison_workspace(dec.h)
+        out_f, lse_f = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n)
+        for rep in range(4):
+            out_w, lse_w = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n, waits=True)
+            if rep == 2:
+                dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n)
+            torch.cuda.synchronize()
+            assert torch.equal(out_w.view(torch.int32), out_f.view(torch.int32)), f"waits != fused (rep {rep})"
+            assert torch.equal(lse_w.view(torch.int32), lse_f.view(torch.int32))
+        assert fd.fd_get_option(dec.h, fd.FD_INFO_WAIT_GAVE_UP) == 0
+        assert all(c == 0 for c in fd.fd_debug_read_counters(dec.h, wl.B * wl.Hkv)), "counters not re-armed"
+    check_out(out_w.cpu().numpy(), ref_o, "waits")
+    check_lse(lse_w.cpu().numpy(), ref_l, "waits")
+
+
+def test_fine_grained_waits_give_up_cleanly_when_told_to():
+    """The bounded wait, forced from the host: with a spin limit of one poll the combine
+    kernel gives up on tiles whose counts are not complete yet; every kernel still ends, the
+    condition is reported, and after fd_reset the handle works again."""
+    wl = _generic(1, 8, 1, 60000, 950)
+    say("case fine-grained waits with FD_OPT_SPIN_LIMIT = 1")
+    inp = fi.make_inputs(wl, "cuda")
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=64) as dec:
+        out_f, lse_f = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 64)
+        fd.fd_set_option(dec.h, fd.FD_OPT_SPIN_LIMIT, 1)
+        dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 64, waits=True)
+        torch.cuda.synchronize()
+        gave_up = fd.fd_get_option(dec.h, fd.FD_INFO_WAIT_GAVE_UP)
+        say(f"  gave up: {gave_up}")
+        fd.fd_set_option(dec.h, fd.FD_OPT_SPIN_LIMIT, 0)
+        fd.fd_reset(dec.h)
+        torch.cuda.synchronize()
+        assert fd.fd_get_option(dec.h, fd.FD_INFO_WAIT_GAVE_UP) == 0
+        out_w, lse_w = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 64, waits=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out_w.view(torch.int32), out_f.view(torch.int32))
+        assert fd.fd_get_option(dec.h, fd.FD_INFO_WAIT_GAVE_UP) == 0
+        pool = torch.zeros(64, 1, 16, 128, device="cuda", dtype=torch.bfloat16)
+        fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 1)
+        with pytest.raises(fd.FdError) as e:
+            dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 64, waits=True)
+        assert e.value.code == fd.FD_ERR_UNSUPPORTED
