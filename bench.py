@@ -240,8 +240,9 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 in, f32 accumulate",
-        "data": "synthetic (seeded N(0,1) bf16 q/K/V; see DESIGN.md input recipe)",
+        "dtype": "bf16",
+        "dtype_detail": "bf16 q/K/V, products and sums in f32 (MFMA f32 accumulate), f32 out and lse",
+        "data": "synthetic (seeded N(0,1) q/K/V rounded to bf16; ragged lengths, scaled K and aligned keys per workload)",
         "config": {"workload": wl.name, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "S_max": wl.S_max,
                    "n_splits": wl.n_splits, "total_keys": int(sl_host.sum()), "kv_copies_rotated": copies,
                    "kv_layout": f"paged, page_size {args.page_size}, random placement" if args.page_size else "contiguous",
