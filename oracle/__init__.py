@@ -44,6 +44,10 @@ def _load():
         lib.fd_oracle_decode.argtypes = [u16p, u16p, u16p, i32p, ctypes.c_int, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_int, ctypes.c_int64,
                                          ctypes.c_double, ctypes.c_int, f64p, f64p]
+        lib.fd_oracle_decode_fmt.restype = ctypes.c_int
+        lib.fd_oracle_decode_fmt.argtypes = lib.fd_oracle_decode.argtypes + [ctypes.c_int]
+        lib.fd_oracle_element.restype = ctypes.c_double
+        lib.fd_oracle_element.argtypes = [ctypes.c_uint16, ctypes.c_int]
         lib.fd_oracle_partial.restype = ctypes.c_int
         lib.fd_oracle_partial.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_int64, ctypes.c_double,
@@ -72,11 +76,19 @@ def max_threads() -> int:
     return int(_load().fd_oracle_max_threads())
 
 
+FORMATS = {"bf16": 0, "fp16": 1}
+
+
+def element(bits: int, fmt: str = "bf16") -> float:
+    """Exact value of one stored 16-bit element."""
+    return float(_load().fd_oracle_element(int(bits), FORMATS[fmt]))
+
+
 def decode(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lens: np.ndarray,
-           scale: float = 0.0, n_threads: int = 0):
+           scale: float = 0.0, n_threads: int = 0, fmt: str = "bf16"):
     """softmax(scale * q K^T) V and LSE for every (b, h).
 
-    q [B,Hq,D], k/v [B,Hkv,S_max,D] as bf16 bits; seq_lens [B] int32.
+    q [B,Hq,D], k/v [B,Hkv,S_max,D] as bf16 (or, fmt="fp16", IEEE half) bits; seq_lens [B] int32.
     Returns (out [B,Hq,D] float64, lse [B,Hq] float64, natural log).
     """
     q = _u16(q, 3, "q")
@@ -91,10 +103,10 @@ def decode(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lens: np.ndarray,
         raise ValueError("seq_lens must have shape [B]")
     out = np.empty((B, Hq, D), dtype=np.float64)
     lse = np.empty((B, Hq), dtype=np.float64)
-    rc = _load().fd_oracle_decode(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16),
-                                  _ptr(v, ctypes.c_uint16), _ptr(sl, ctypes.c_int32),
-                                  B, Hq, Hkv, D, S_max, float(scale), int(n_threads),
-                                  _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    rc = _load().fd_oracle_decode_fmt(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16),
+                                      _ptr(v, ctypes.c_uint16), _ptr(sl, ctypes.c_int32),
+                                      B, Hq, Hkv, D, S_max, float(scale), int(n_threads),
+                                      _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double), FORMATS[fmt])
     if rc != 0:
         raise ValueError("fd_oracle_decode rejected its arguments")
     return out, lse
@@ -138,7 +150,7 @@ def merge(part_o: np.ndarray, part_lse: np.ndarray):
 
 
 def decode_paged(q: np.ndarray, k_pages: np.ndarray, v_pages: np.ndarray, block_table: np.ndarray,
-                 seq_lens: np.ndarray, scale: float = 0.0, n_threads: int = 0):
+                 seq_lens: np.ndarray, scale: float = 0.0, n_threads: int = 0, fmt: str = "bf16"):
     """The same attention over a paged KV cache, by its definition: key j of sequence b is
     row j % page_size of page block_table[b, j // page_size].
 
@@ -170,4 +182,4 @@ def decode_paged(q: np.ndarray, k_pages: np.ndarray, v_pages: np.ndarray, block_
                 raise ValueError(f"block_table[{b}, {j // page_size}] = {page} is not a page")
             k[b, :, j, :] = kp[page, :, j % page_size, :]
             v[b, :, j, :] = vp[page, :, j % page_size, :]
-    return decode(q, k, v, sl.astype(np.int32), scale=scale, n_threads=n_threads)
+    return decode(q, k, v, sl.astype(np.int32), scale=scale, n_threads=n_threads, fmt=fmt)

@@ -54,6 +54,27 @@ static double bf16_bits_to_double(uint16_t bits)
 }
 
 /*
+ * IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) widened exactly: the paper's own
+ * precision (Section 5.1 runs its kernels in FP16).  Subnormals are f * 2^-24, exponent 31
+ * is infinity / NaN.
+ */
+static double fp16_bits_to_double(uint16_t bits)
+{
+    const int sign = bits >> 15, e = (bits >> 10) & 31, f = bits & 1023;
+    double mag;
+    if (e == 0) mag = ldexp((double)f, -24);
+    else if (e == 31) mag = f ? NAN : INFINITY;
+    else mag = ldexp((double)(1024 + f), e - 25);
+    return sign ? -mag : mag;
+}
+
+/* fmt 0: bf16 bit patterns, 1: fp16 bit patterns */
+static double elem_to_double(uint16_t bits, int fmt)
+{
+    return fmt == 1 ? fp16_bits_to_double(bits) : bf16_bits_to_double(bits);
+}
+
+/*
  * Attention of query row (b, h) over keys j in [j0, j1) of its KV head.
  * scores: caller-provided scratch of at least (j1 - j0) doubles.
  * Writes out_row[D] and *lse_row.  Empty range: zeros and -inf.
@@ -61,7 +82,7 @@ static double bf16_bits_to_double(uint16_t bits)
 static void attend_range(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                          int Hq, int Hkv, int D, int64_t S_max, double scale,
                          int b, int h, int64_t j0, int64_t j1,
-                         double* scores, double* out_row, double* lse_row)
+                         double* scores, double* out_row, double* lse_row, int fmt)
 {
     const int G = Hq / Hkv;
     const int kvh = h / G;
@@ -81,7 +102,7 @@ static void attend_range(const uint16_t* q, const uint16_t* k, const uint16_t* v
         const uint16_t* krow = kbase + j * D;
         double dot = 0.0;
         for (int d = 0; d < D; ++d)
-            dot += bf16_bits_to_double(qrow[d]) * bf16_bits_to_double(krow[d]);
+            dot += elem_to_double(qrow[d], fmt) * elem_to_double(krow[d], fmt);
         double s = scale * dot;
         scores[j - j0] = s;
         if (s > m) m = s;
@@ -93,7 +114,7 @@ static void attend_range(const uint16_t* q, const uint16_t* k, const uint16_t* v
     for (int64_t j = j0; j < j1; ++j) {
         const double w = exp(scores[j - j0] - m) / l;
         const uint16_t* vrow = vbase + j * D;
-        for (int d = 0; d < D; ++d) out_row[d] += w * bf16_bits_to_double(vrow[d]);
+        for (int d = 0; d < D; ++d) out_row[d] += w * elem_to_double(vrow[d], fmt);
     }
     *lse_row = m + log(l);
 }
@@ -103,12 +124,12 @@ static void attend_range(const uint16_t* q, const uint16_t* k, const uint16_t* v
  * n_threads <= 0 means the OpenMP default.  Returns 0, or -1 on bad arguments
  * or allocation failure.
  */
-int fd_oracle_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                     const int32_t* seq_lens, int B, int Hq, int Hkv, int D,
-                     int64_t S_max, double scale, int n_threads,
-                     double* out, double* lse)
+int fd_oracle_decode_fmt(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                         const int32_t* seq_lens, int B, int Hq, int Hkv, int D,
+                         int64_t S_max, double scale, int n_threads,
+                         double* out, double* lse, int fmt)
 {
-    if (!q || !k || !v || !seq_lens || !out || !lse) return -1;
+    if (!q || !k || !v || !seq_lens || !out || !lse || fmt < 0 || fmt > 1) return -1;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || S_max <= 0 || Hq % Hkv) return -1;
     for (int b = 0; b < B; ++b)
         if (seq_lens[b] < 0 || seq_lens[b] > S_max) return -1;
@@ -133,12 +154,24 @@ int fd_oracle_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v,
             if (!scores) continue;
             const int b = r / Hq, h = r % Hq;
             attend_range(q, k, v, Hq, Hkv, D, S_max, scale, b, h, 0, seq_lens[b],
-                         scores, out + (int64_t)r * D, lse + r);
+                         scores, out + (int64_t)r * D, lse + r, fmt);
         }
         free(scores);
     }
     return failed ? -1 : 0;
 }
+
+/* The same for bf16 bit patterns (the benchmark's format). */
+int fd_oracle_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                     const int32_t* seq_lens, int B, int Hq, int Hkv, int D,
+                     int64_t S_max, double scale, int n_threads,
+                     double* out, double* lse)
+{
+    return fd_oracle_decode_fmt(q, k, v, seq_lens, B, Hq, Hkv, D, S_max, scale, n_threads, out, lse, 0);
+}
+
+/* Exact value of one stored element (for tests of the two formats). */
+double fd_oracle_element(uint16_t bits, int fmt) { return elem_to_double(bits, fmt); }
 
 /*
  * Attention of one query row (b, h) restricted to keys [j0, j1): the
@@ -156,7 +189,7 @@ int fd_oracle_partial(const uint16_t* q, const uint16_t* k, const uint16_t* v,
     if (scale <= 0.0) scale = 1.0 / sqrt((double)D);
     double* scores = (double*)malloc(sizeof(double) * (size_t)(j1 > j0 ? j1 - j0 : 1));
     if (!scores) return -1;
-    attend_range(q, k, v, Hq, Hkv, D, S_max, scale, b, h, j0, j1, scores, out_row, lse_row);
+    attend_range(q, k, v, Hq, Hkv, D, S_max, scale, b, h, j0, j1, scores, out_row, lse_row, 0);
     free(scores);
     return 0;
 }

@@ -457,3 +457,43 @@ def test_make_paged_round_trips_through_the_oracle():
         o, l = oracle.decode_paged(fi.bits(pg.q), fi.bits(pg.k_pages), fi.bits(pg.v_pages),
                                    pg.block_table.numpy(), pg.seq_lens.numpy())
         assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
+
+
+# ---- fp16 inputs: the oracle's half -> double widening against numpy's and fixed patterns ----
+
+def test_fp16_widening_matches_numpy_for_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.element(int(b), "fp16") for b in bits])
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan]))          # -0.0 stays -0.0
+
+
+def test_fp16_and_bf16_fixed_patterns():
+    for bits, val in ((0x3C00, 1.0), (0xC000, -2.0), (0x7BFF, 65504.0), (0x0001, 2.0 ** -24), (0x0400, 2.0 ** -14),
+                      (0x3555, 0.333251953125)):
+        assert oracle.element(bits, "fp16") == val
+    for bits, val in ((0x3F80, 1.0), (0xC000, -2.0), (0x3EAB, 0.333984375)):
+        assert oracle.element(bits, "bf16") == val
+
+
+def test_fp16_decode_equals_fp64_reference_on_the_widened_values():
+    """The fp16 path against torch's fp64 attention on the exactly widened inputs (library pin)."""
+    rng = np.random.default_rng(21)
+    B, Hq, Hkv, S, D = 2, 4, 2, 37, 16
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    k = rng.standard_normal((B, Hkv, S, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hkv, S, D)).astype(np.float16)
+    sl = np.array([S, 20], dtype=np.int32)
+    o, l = oracle.decode(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), sl, fmt="fp16")
+    for b in range(B):
+        n = int(sl[b])
+        qt = torch.from_numpy(q[b].astype(np.float64))                      # [Hq, D]
+        kt = torch.from_numpy(k[b, :, :n].astype(np.float64)).repeat_interleave(Hq // Hkv, 0)
+        vt = torch.from_numpy(v[b, :, :n].astype(np.float64)).repeat_interleave(Hq // Hkv, 0)
+        s = torch.einsum("hd,hjd->hj", qt, kt) / math.sqrt(D)
+        ref = torch.einsum("hj,hjd->hd", torch.softmax(s, -1), vt).numpy()
+        assert np.allclose(o[b], ref, rtol=1e-12, atol=1e-13)
+        assert np.allclose(l[b], torch.logsumexp(s, -1).numpy(), rtol=1e-12, atol=1e-13)
