@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
     ap.add_argument("--ring-stages", type=int, default=0)
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16"], help="element type of q/K/V (fp16 = the paper's)")
     ap.add_argument("--autotune", action="store_true",
                     help="let fd_autotune pick the options for this shape first (untimed); the choice is reported")
     ap.add_argument("--page-size", type=int, default=0,
@@ -111,7 +112,7 @@ def read_traffic(workload_name):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(inp, wl, fi):
+def cpu_baseline(inp, wl, fi, fmt="bf16"):
     """The fp64 oracle as it stands, timed on the host cores on a bounded sample of the workload."""
     import numpy as np
     import oracle
@@ -124,11 +125,11 @@ def cpu_baseline(inp, wl, fi):
         acc += int(sl[B]) * wl.Hq
         B += 1
     q, k, v = fi.bits(inp.q[:B]), fi.bits(inp.k[:B]), fi.bits(inp.v[:B])
-    oracle.decode(q[:1, :, :], k[:1, :, :64].copy(), v[:1, :, :64].copy(), np.minimum(sl[:1], 64))   # load + warm
+    oracle.decode(q[:1, :, :], k[:1, :, :64].copy(), v[:1, :, :64].copy(), np.minimum(sl[:1], 64), fmt=fmt)   # load + warm
     t0 = time.perf_counter()
     reps = 0
     while True:
-        oracle.decode(q, k, v, sl[:B])
+        oracle.decode(q, k, v, sl[:B], fmt=fmt)
         reps += 1
         if time.perf_counter() - t0 > 10.0 or reps >= 20:
             break
@@ -154,7 +155,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     wl = fi.workload(args.config)
-    inp = fi.make_inputs(wl, "cuda")
+    inp = fi.make_inputs(wl, "cuda", dtype=torch.float16 if args.dtype == "fp16" else torch.bfloat16)
     sl_host = inp.seq_lens.cpu().numpy()
     alg_bytes = fi.algorithmic_bytes(wl, sl_host)
     kv_bytes = inp.k.numel() * 2 * 2
@@ -163,7 +164,7 @@ def main():
     ks = [inp.k] + [inp.k.clone() for _ in range(copies - 1)]
     vs = [inp.v] + [inp.v.clone() for _ in range(copies - 1)]
     max_splits = wl.n_splits if wl.n_splits > 0 else -(-wl.S_max // 512)
-    dec = fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max_splits)
+    dec = fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max_splits, dtype=args.dtype)
     for key, val in ((fd.FD_OPT_XCD_GROUPS, args.xcd_groups), (fd.FD_OPT_WGS_PER_CU, args.wgs_per_cu),
                      (fd.FD_OPT_PATH, args.path), (fd.FD_OPT_RING_STAGES, args.ring_stages)):
         if val:
@@ -217,7 +218,7 @@ def main():
         bsp_ms, _ = time_calls(bsp, args.warmup, args.steps, torch)
 
     waits_ms = None
-    if not args.no_waits and not args.page_size and path == 2:
+    if not args.no_waits and not args.page_size and path == 2 and args.dtype == "bf16":
         def waits(i):
             j = i % copies
             fd.fd_decode_waits(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
@@ -240,8 +241,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
-        "dtype_detail": "bf16 q/K/V, products and sums in f32 (MFMA f32 accumulate), f32 out and lse",
+        "dtype": args.dtype,
+        "dtype_detail": f"{args.dtype} q/K/V, products and sums in f32 (MFMA f32 accumulate), f32 out and lse",
         "data": "synthetic (seeded N(0,1) q/K/V rounded to bf16; ragged lengths, scaled K and aligned keys per workload)",
         "config": {"workload": wl.name, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "S_max": wl.S_max,
                    "n_splits": wl.n_splits, "total_keys": int(sl_host.sum()), "kv_copies_rotated": copies,
@@ -263,7 +264,7 @@ def main():
                      "kernel": "fd fused persistent kernel (one launch per call)"},
     }
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(inp, wl, fi)
+        rec["cpu_baseline"] = cpu_baseline(inp, wl, fi, args.dtype)
     dec.close()
     print(json.dumps(rec))
 

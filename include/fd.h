@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define FD_VERSION 110
+#define FD_VERSION 120
 
 enum {
     FD_OK = 0,
@@ -67,13 +67,22 @@ typedef struct fd_handle_s* fd_handle_t;
  *   kv_layout   0 = contiguous [B, Hkv, S_max, D] (the only layout)
  *   scale       softmax scale; 0 means 1/sqrt(D).  Applied in fp32 to the
  *               fp32 dot product (never folded into a re-rounded bf16 q).
+ *   dtype       FD_DTYPE_BF16 (the benchmark's format) or FD_DTYPE_FP16 (IEEE half, the
+ *               paper's format, Section 5.1): wherever the comments below say bf16, read
+ *               "dtype".  Half inputs run on the MFMA kernel only (FD_OPT_PATH = 1 and
+ *               fd_decode_waits are FD_ERR_UNSUPPORTED); sums are fp32 either way.
  */
 typedef struct {
     int32_t B, Hq, Hkv, D, S_max;
     int32_t max_splits;
     int32_t kv_layout;
     float scale;
+    int32_t dtype;
 } fd_config;
+
+/* fd_config.dtype: element type of q, k_cache, v_cache (out and lse are always fp32). */
+#define FD_DTYPE_BF16 0
+#define FD_DTYPE_FP16 1
 
 /* Bytes of device workspace fd_create() allocates for cfg (0 if cfg is invalid). */
 size_t fd_workspace_bytes(const fd_config* cfg);

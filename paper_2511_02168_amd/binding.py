@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libfd.so")
 
 FD_OK, FD_ERR_INVALID_ARG, FD_ERR_UNSUPPORTED, FD_ERR_WORKSPACE, FD_ERR_HIP = 0, -1, -2, -3, -4
 FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES, FD_OPT_SPIN_LIMIT = 1, 2, 3, 4, 5
+FD_DTYPE_BF16, FD_DTYPE_FP16 = 0, 1
 FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH, FD_INFO_WAIT_GAVE_UP = 100, 101, 102, 103
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
@@ -28,7 +29,7 @@ EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_deco
 class fd_config(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("S_max", ctypes.c_int32), ("max_splits", ctypes.c_int32),
-                ("kv_layout", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("kv_layout", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
 
 
 class FdError(RuntimeError):
@@ -190,8 +191,8 @@ class FlashDecode:
     """Convenience owner of one handle: shapes fixed at construction."""
 
     def __init__(self, B: int, Hq: int, Hkv: int, S_max: int, max_splits: int = 256, D: int = 128,
-                 scale: float = 0.0):
-        self.cfg = fd_config(B, Hq, Hkv, D, S_max, max_splits, 0, scale)
+                 scale: float = 0.0, dtype: str = "bf16"):
+        self.cfg = fd_config(B, Hq, Hkv, D, S_max, max_splits, 0, scale, {"bf16": FD_DTYPE_BF16, "fp16": FD_DTYPE_FP16}[dtype])
         self.h = fd_create(self.cfg)
 
     def close(self) -> None:
@@ -215,7 +216,8 @@ class FlashDecode:
         import torch
         c = self.cfg
         assert q.is_cuda and k.is_cuda and v.is_cuda and seq_lens.is_cuda and out.is_cuda
-        assert q.dtype == torch.bfloat16 and k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
+        want = torch.float16 if c.dtype == FD_DTYPE_FP16 else torch.bfloat16
+        assert q.dtype == want and k.dtype == want and v.dtype == want
         assert seq_lens.dtype == torch.int32 and out.dtype == torch.float32
         assert tuple(q.shape) == (c.B, c.Hq, c.D) and q.is_contiguous()
         assert tuple(k.shape) == (c.B, c.Hkv, c.S_max, c.D) and k.is_contiguous()
@@ -249,11 +251,12 @@ class FlashDecode:
         if lse is None and want_lse:
             lse = torch.empty(c.B, c.Hq, device=q.device, dtype=torch.float32)
         assert k_pages.is_cuda and v_pages.is_cuda and block_table.is_cuda and q.is_cuda and seq_lens.is_cuda
-        assert k_pages.dtype == torch.bfloat16 and v_pages.dtype == torch.bfloat16 and block_table.dtype == torch.int32
+        want = torch.float16 if c.dtype == FD_DTYPE_FP16 else torch.bfloat16
+        assert k_pages.dtype == want and v_pages.dtype == want and block_table.dtype == torch.int32
         assert k_pages.shape == v_pages.shape and k_pages.is_contiguous() and v_pages.is_contiguous()
         assert tuple(k_pages.shape[1:]) == (c.Hkv, page_size, c.D)
         assert block_table.dim() == 2 and block_table.shape[0] == c.B and block_table.is_contiguous()
-        assert tuple(q.shape) == (c.B, c.Hq, c.D) and q.is_contiguous() and q.dtype == torch.bfloat16
+        assert tuple(q.shape) == (c.B, c.Hq, c.D) and q.is_contiguous() and q.dtype == want
         assert tuple(seq_lens.shape) == (c.B,) and seq_lens.dtype == torch.int32 and seq_lens.is_contiguous()
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream

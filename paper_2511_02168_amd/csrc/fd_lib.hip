@@ -34,14 +34,14 @@ struct ValuPath {
 };
 
 // ... or on the matrix cores, through an LDS ring of NST stages per wave.
-template <int NST, bool PAGED>
+template <int NST, bool PAGED, bool F16>
 struct MfmaPath {
     char* ring;
     template <bool SHARED>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
                                          float mul) const
     {
-        mfma_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+        mfma_item<NST, PAGED, F16, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
     }
 };
 
@@ -168,12 +168,13 @@ extern __shared__ __attribute__((aligned(16))) char fd_dyn_smem[];
 // CB = rows a combining thread keeps in flight: 32 when the workgroup has the CU to itself
 // (512 registers per lane), 8 when two workgroups share it.
 // PAGED: K/V rows are found through p.block_table (built for NST = 2 only).
-template <int NST, bool FUSED, int CB, bool PAGED>
+// F16: IEEE half q/K/V instead of bf16 (built for NST = 2 only).
+template <int NST, bool FUSED, int CB, bool PAGED, bool F16>
 __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 {
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
-    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, MfmaPath<NST, PAGED>{fd_dyn_smem}, ss,
+    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, MfmaPath<NST, PAGED, F16>{fd_dyn_smem}, ss,
                                                         *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_signal_kernel(Params p)
 {
     __shared__ SchedSmem ss;
-    persistent_loop<kModeSignal, 8>(p, MfmaPath<2, false>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+    persistent_loop<kModeSignal, 8>(p, MfmaPath<2, false, false>{fd_dyn_smem}, ss, *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
 // Kernel 2 of the bulk-synchronous baseline: one workgroup per tile.
@@ -335,6 +336,8 @@ int check_config(const fd_config* c)
     if (!(c->scale >= 0.0f) || std::isinf(c->scale)) return fail(FD_ERR_INVALID_ARG, "scale must be finite and >= 0");
     if (c->D != fd::kD) return fail(FD_ERR_UNSUPPORTED, "only D = 128 is built (got %d)", c->D);
     if (c->kv_layout != 0) return fail(FD_ERR_UNSUPPORTED, "only kv_layout 0 ([B,Hkv,S_max,D]) is built");
+    if (c->dtype != FD_DTYPE_BF16 && c->dtype != FD_DTYPE_FP16)
+        return fail(FD_ERR_UNSUPPORTED, "dtype must be FD_DTYPE_BF16 (0) or FD_DTYPE_FP16 (1), got %d", c->dtype);
     const int G = c->Hq / c->Hkv;
     if (G > 16) return fail(FD_ERR_UNSUPPORTED, "GQA group Hq/Hkv = %d is not built (1..16)", G);
     if ((long long)c->B * c->Hkv > (1ll << 24)) return fail(FD_ERR_UNSUPPORTED, "B*Hkv too large");
@@ -389,7 +392,7 @@ int launch_valu(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
-template <int NST, int CB, bool PAGED>
+template <int NST, int CB, bool PAGED, bool F16>
 int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
 {
     // more than 64 KB of dynamic LDS has to be granted once per kernel and device
@@ -399,19 +402,19 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     const size_t ring = (size_t)fd::mfma_lds_bytes(NST);      // ring + page-number slots
     if (granted_device[fused] != dev) {
         if (fused)
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true, CB, PAGED>,
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, true, CB, PAGED, F16>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
         else
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false, CB, PAGED>,
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma_kernel<NST, false, CB, PAGED, F16>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring));
         granted_device[fused] = dev;
     }
     if (fused) {
-        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+        hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, true, CB, PAGED, F16>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
         FD_HIP(hipGetLastError());
         return FD_OK;
     }
-    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
+    hipLaunchKernelGGL((fd::fd_mfma_kernel<NST, false, CB, PAGED, F16>), dim3(grid), dim3(fd::kWgThreads), ring, st, p);
     FD_HIP(hipGetLastError());
     return launch_combine(p, st);
 }
@@ -487,6 +490,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         if (path == 1) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel does not read paged caches");
         path = 2;
     }
+    if (c.dtype == FD_DTYPE_FP16) {
+        if (path == 1) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for bf16 only");
+        if (mode == fd::kModeSignal) return fail(FD_ERR_UNSUPPORTED, "the fine-grained-waits variant is built for bf16 only");
+        path = 2;
+    }
     if (path == 0) path = 2;
     if (mode == fd::kModeSignal) {
         if (path != 2 || pg.table) return fail(FD_ERR_UNSUPPORTED, "the fine-grained-waits variant exists for the MFMA kernel on a contiguous cache only");
@@ -548,13 +556,21 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     if (path == 2) {
         int nst = h->opt_ring > 0 ? h->opt_ring : 2;
         if (per_cu > 1) nst = 2;                       // two workgroups per CU share the LDS
-        if (pg.table)                                  // the paged kernels are built for the default ring depth
-            return per_cu > 1 ? launch_mfma<2, 8, true>(p, fused, (int)grid, st)
-                              : launch_mfma<2, 32, true>(p, fused, (int)grid, st);
-        if (per_cu > 1) return launch_mfma<2, 8, false>(p, fused, (int)grid, st);
-        if (nst == 4) return launch_mfma<4, 32, false>(p, fused, (int)grid, st);
-        if (nst == 3) return launch_mfma<3, 32, false>(p, fused, (int)grid, st);
-        return launch_mfma<2, 32, false>(p, fused, (int)grid, st);
+        const bool two = per_cu > 1;
+        if (h->cfg.dtype == FD_DTYPE_FP16) {           // the half and the paged kernels are built for the default ring depth
+            if (pg.table)
+                return two ? launch_mfma<2, 8, true, true>(p, fused, (int)grid, st)
+                           : launch_mfma<2, 32, true, true>(p, fused, (int)grid, st);
+            return two ? launch_mfma<2, 8, false, true>(p, fused, (int)grid, st)
+                       : launch_mfma<2, 32, false, true>(p, fused, (int)grid, st);
+        }
+        if (pg.table)
+            return two ? launch_mfma<2, 8, true, false>(p, fused, (int)grid, st)
+                       : launch_mfma<2, 32, true, false>(p, fused, (int)grid, st);
+        if (two) return launch_mfma<2, 8, false, false>(p, fused, (int)grid, st);
+        if (nst == 4) return launch_mfma<4, 32, false, false>(p, fused, (int)grid, st);
+        if (nst == 3) return launch_mfma<3, 32, false, false>(p, fused, (int)grid, st);
+        return launch_mfma<2, 32, false, false>(p, fused, (int)grid, st);
     }
     switch (G) {
         case 1: return launch_valu<1>(p, fused, (int)grid, st);

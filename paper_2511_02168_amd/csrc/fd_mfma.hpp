@@ -42,6 +42,8 @@ __host__ __device__ constexpr int mfma_lds_bytes(int nst) { return mfma_ring_byt
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
@@ -127,7 +129,9 @@ __device__ __forceinline__ void mfma_issue_stage(uint32_t lds_stage, const uint1
 }
 
 // One landed stage: scores, online softmax, PV.
-template <bool MASKED>
+// F16: q, K, V hold IEEE half instead of bf16; the same tiles through the f16 MFMAs, P split
+// into half hi + lo (p in [0, 1]: the lo part keeps it to ~2^-21, flushing below 6e-8).
+template <bool MASKED, bool F16>
 __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16x8_t (&qb)[4], MfmaState& st,
                                                    float scale_log2, int kb, int j1, int lane)
 {
@@ -139,7 +143,11 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
     for (int t = 0; t < 4; ++t) {
         const int chunk = 4 * t + kg;
         const uint4 kk = *reinterpret_cast<const uint4*>(stage + i16 * 256 + ((chunk ^ i16) << 4));
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kk), qb[t], s, 0, 0, 0);
+        if (F16)
+            s = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, kk), __builtin_bit_cast(f16x8_t, qb[t]), s,
+                                                       0, 0, 0);
+        else
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kk), qb[t], s, 0, 0, 0);
     }
     // now s[e] = <q_head, K[kb + 4kg + e]> for head = lane & 15
 
@@ -166,10 +174,17 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
     for (int e = 0; e < 4; ++e) {
         p[e] = fast_exp2(p[e] - st.m);
         st.l += p[e];
-        const __bf16 hi = (__bf16)p[e];
-        const __bf16 lo = (__bf16)(p[e] - (float)hi);
-        phi[e] = __builtin_bit_cast(short, hi);
-        plo[e] = __builtin_bit_cast(short, lo);
+        if (F16) {
+            const _Float16 hi = (_Float16)p[e];
+            const _Float16 lo = (_Float16)(p[e] - (float)hi);
+            phi[e] = __builtin_bit_cast(short, hi);
+            plo[e] = __builtin_bit_cast(short, lo);
+        } else {
+            const __bf16 hi = (__bf16)p[e];
+            const __bf16 lo = (__bf16)(p[e] - (float)hi);
+            phi[e] = __builtin_bit_cast(short, hi);
+            plo[e] = __builtin_bit_cast(short, lo);
+        }
     }
 
     // a5: O^T[dim][head] += V^T . P^T, 16 dims at a time.  Lane t of a 16-lane group
@@ -183,8 +198,14 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
         const int chunk = 2 * db + (vsub >> 1);
         const char* src = vstage + vrow * 256 + ((chunk ^ vrow) << 4) + ((vsub & 1) << 3);
         const s16x4_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)src);
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, phi, st.acc[db], 0, 0, 0);
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, plo, st.acc[db], 0, 0, 0);
+        if (F16) {
+            const f16x4_t vh = __builtin_bit_cast(f16x4_t, vt);
+            st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16f16(vh, __builtin_bit_cast(f16x4_t, phi), st.acc[db], 0, 0, 0);
+            st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16f16(vh, __builtin_bit_cast(f16x4_t, plo), st.acc[db], 0, 0, 0);
+        } else {
+            st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, phi, st.acc[db], 0, 0, 0);
+            st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, plo, st.acc[db], 0, 0, 0);
+        }
     }
 }
 
@@ -193,7 +214,7 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
 // it doubles as the ItemSmem<16> staging at the end of the range.
 // Writes the normalised result to dst_o[G][D] and the log-sum-exp times lse_mul to
 // dst_lse[G] (SHARED as in item_finish).  Leaves LDS free for reuse on return.
-template <int NST, bool PAGED, bool SHARED>
+template <int NST, bool PAGED, bool F16, bool SHARED>
 __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
                                  float lse_mul, char* ring)
 {
@@ -284,8 +305,8 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kMfBlockKeys;
             const char* stage = my_ring + (s % NST) * kMfStageBytes;
-            if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
-            else mfma_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+            if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false, F16>(stage, qb, st, sl2, kb, j1, lane);
+            else mfma_consume_stage<true, F16>(stage, qb, st, sl2, kb, j1, lane);
         }
     }
 

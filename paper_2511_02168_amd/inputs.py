@@ -80,8 +80,8 @@ class Inputs:
 
 
 def bits(t: torch.Tensor) -> np.ndarray:
-    """Exact bf16 bit patterns of a bf16 tensor as a host uint16 array."""
-    assert t.dtype == torch.bfloat16
+    """Exact bit patterns of a bf16 (or fp16) tensor as a host uint16 array."""
+    assert t.dtype in (torch.bfloat16, torch.float16)
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
@@ -128,7 +128,7 @@ def _align_keys(k32: torch.Tensor, q32: torch.Tensor, frac: float, gen: torch.Ge
 
 
 def make_inputs(wl: Workload, device="cpu", S_max: Optional[int] = None,
-                B: Optional[int] = None, nan_pad: bool = True) -> Inputs:
+                B: Optional[int] = None, nan_pad: bool = True, dtype: torch.dtype = torch.bfloat16) -> Inputs:
     """Draw q, K, V ~ N(0,1) (K scaled by wl.k_scale), round to bf16.
 
     S_max / B override the workload's sizes (for reduced copies the oracle can
@@ -142,13 +142,13 @@ def make_inputs(wl: Workload, device="cpu", S_max: Optional[int] = None,
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.seed)
     q32 = torch.randn(Bn, wl.Hq, wl.D, generator=gen, device=dev, dtype=torch.float32)
-    q = q32.to(torch.bfloat16)
+    q = q32.to(dtype)
     if wl.ragged:
         sl = torch.randint(1, S + 1, (Bn,), generator=gen, device=dev, dtype=torch.int32)
     else:
         sl = torch.full((Bn,), S, device=dev, dtype=torch.int32)
-    k = torch.empty(Bn, wl.Hkv, S, wl.D, device=dev, dtype=torch.bfloat16)
-    v = torch.empty(Bn, wl.Hkv, S, wl.D, device=dev, dtype=torch.bfloat16)
+    k = torch.empty(Bn, wl.Hkv, S, wl.D, device=dev, dtype=dtype)
+    v = torch.empty(Bn, wl.Hkv, S, wl.D, device=dev, dtype=dtype)
     sl_host = sl.cpu().tolist()
     for b in range(Bn):                      # one batch entry at a time bounds the fp32 temporaries
         k32 = torch.randn(wl.Hkv, S, wl.D, generator=gen, device=dev, dtype=torch.float32)
@@ -161,8 +161,8 @@ def make_inputs(wl: Workload, device="cpu", S_max: Optional[int] = None,
         if wl.ragged and nan_pad and sl_host[b] < S:
             k32[:, sl_host[b]:, :] = float("nan")
             v32[:, sl_host[b]:, :] = float("nan")
-        k[b] = k32.to(torch.bfloat16)
-        v[b] = v32.to(torch.bfloat16)
+        k[b] = k32.to(dtype)
+        v[b] = v32.to(dtype)
     return Inputs(q=q, k=k, v=v, seq_lens=sl, wl=wl)
 
 
@@ -192,8 +192,8 @@ def make_paged(inp: Inputs, page_size: int, seed: int = 0) -> PagedInputs:
     gen.manual_seed(1000003 * page_size + seed)
     slots = torch.randperm(n_used, generator=gen).tolist()
     nan_page = n_used
-    k_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=torch.bfloat16)
-    v_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=torch.bfloat16)
+    k_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=inp.k.dtype)
+    v_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=inp.k.dtype)
     table = torch.full((B, max_pages), nan_page, dtype=torch.int32)
     it = iter(slots)
     for b in range(B):

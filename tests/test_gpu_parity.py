@@ -609,3 +609,53 @@ def test_fine_grained_waits_give_up_cleanly_when_told_to():
         with pytest.raises(fd.FdError) as e:
             dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 64, waits=True)
         assert e.value.code == fd.FD_ERR_UNSUPPORTED
+
+
+# ---------------------------------------------------------------- IEEE half inputs
+
+@pytest.mark.parametrize("shape", [(2, 8, 8, 1000, 4), (3, 16, 2, 2500, 0), (2, 12, 4, 777, 3), (1, 16, 1, 30000, 37),
+                                   (2, 32, 2, 513, 0)])
+def test_half_inputs(shape):
+    """dtype = FD_DTYPE_FP16 (the paper's precision): same tolerances against the oracle reading
+    the same half bit patterns; fused and BSP bitwise equal; paged as well."""
+    B, Hq, Hkv, S, n = shape
+    wl = _generic(B, Hq, Hkv, S, 1200 + S + Hq, ragged=(n == 0))
+    say(f"case half inputs B{B} Hq{Hq} Hkv{Hkv} S{S} n{n}")
+    inp = fi.make_inputs(wl, "cuda", dtype=torch.float16)
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy(), fmt="fp16")
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max(n, 8), dtype="fp16") as dec:
+        fd.fd_debug_poison_workspace(dec.h)
+        out, lse = run_both(dec, inp, n)
+        eo = check_out(out, ref_o, "half")
+        el = check_lse(lse, ref_l, "half")
+        say(f"  max |out err| {eo:.2e}, max |lse err| {el:.2e}")
+        pg = fi.make_paged(inp, 32, seed=1)
+        out_p, lse_p = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, 32, pg.seq_lens, n)
+        out_pb, _ = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, 32, pg.seq_lens, n, bsp=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out_p.view(torch.int32), out_pb.view(torch.int32))
+        check_out(out_p.cpu().numpy(), ref_o, "half paged")
+        check_lse(lse_p.cpu().numpy(), ref_l, "half paged")
+        fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 1)
+        with pytest.raises(fd.FdError) as e:
+            dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n)
+        assert e.value.code == fd.FD_ERR_UNSUPPORTED
+        fd.fd_set_option(dec.h, fd.FD_OPT_PATH, 0)
+        with pytest.raises(fd.FdError) as e:
+            dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n, waits=True)
+        assert e.value.code == fd.FD_ERR_UNSUPPORTED
+
+
+def test_half_inputs_peaked_attention():
+    """Two dominant keys with opposite values in half precision (weights near 0.5 each, everything else tiny)."""
+    wl = _generic(1, 8, 1, 4096, 1300)
+    inp = fi.make_inputs(wl, "cuda", dtype=torch.float16)
+    inp.k[0, 0, 100] = inp.q[0, 0] * 3.0
+    inp.k[0, 0, 3000] = inp.q[0, 0] * 3.0
+    inp.v[0, 0, 100] = 50.0
+    inp.v[0, 0, 3000] = -50.0
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy(), fmt="fp16")
+    with fd.FlashDecode(1, 8, 1, 4096, max_splits=16, dtype="fp16") as dec:
+        out, lse = run_both(dec, inp, 16)
+    check_out(out, ref_o, "half peaked")
+    check_lse(lse, ref_l, "half peaked")
