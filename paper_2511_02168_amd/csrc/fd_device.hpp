@@ -205,14 +205,15 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 
 // ---- exchange of partials between workgroups ----------------------------------
 // A gfx950 device has 8 XCDs, each with its own L2 that is not kept coherent
-// with the others.  An agent-scope release/acquire FENCE is implemented as a
-// write-back / invalidate of a whole L2, far too heavy to run once per item.
-// Partials and counters are therefore written and read only with agent-scope
-// relaxed atomic accesses (sc1 stores write through to the device-coherent
-// level, sc1 loads do not use a possibly stale L1/L2 line), and the order
-// "partials, then counter" is kept by waiting for the stores' acknowledgements
+// with the others.  An agent-scope release FENCE writes back a whole L2, far too
+// heavy to run once per item.  A workgroup therefore WRITES its partial with
+// agent-scope stores (sc1: written through to the device-coherent level) and keeps
+// the order "partial, then counter" by waiting for the stores' acknowledgements
 // (s_waitcnt vmcnt(0)) before the workgroup barrier that precedes the counter
-// increment.  No other data travels between workgroups inside a launch.
+// increment.  The one workgroup that READS a tile's partials does so after seeing the
+// complete count: first head 0's lse per slot with agent-scope loads where it scans for
+// live slots, then one acquire fence (invalidate only: nothing to write back) and
+// ordinary loads for the rows.  No other data travels between workgroups in a launch.
 __device__ __forceinline__ void store_agent(float* p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -226,13 +227,6 @@ __device__ __forceinline__ void store_agent4(float* p, f32x4 v)
 __device__ __forceinline__ float load_agent(const float* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// two adjacent floats (8-byte aligned) in one coherent access
-__device__ __forceinline__ float2 load_agent2(const float* p)
-{
-    const unsigned long long w =
-        __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__builtin_bit_cast(float, (uint32_t)w), __builtin_bit_cast(float, (uint32_t)(w >> 32)));
 }
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -252,8 +246,7 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
-// Maximum / sum over the 64 lanes: DPP inside each row of 16, then the 4 row results
-// are read from one lane each (no LDS traffic).  Every lane gets the result.
+// Maximum over each row of 16 lanes (DPP only, every lane of the row gets it).
 __device__ __forceinline__ float row16_max(float x)
 {
     x = fmaxf(x, dpp_f32<0xB1>(x));
@@ -261,23 +254,6 @@ __device__ __forceinline__ float row16_max(float x)
     x = fmaxf(x, dpp_f32<0x141>(x));
     x = fmaxf(x, dpp_f32<0x140>(x));
     return x;
-}
-
-__device__ __forceinline__ float lane_value(float x, int lane)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
-}
-
-__device__ __forceinline__ float wave_max(float x)
-{
-    x = row16_max(x);
-    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
-}
-
-__device__ __forceinline__ float wave_sum(float x)
-{
-    x = row16_sum(x);
-    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
 
 // ---- end of an item: merge the workgroup's 4 wave states, normalise, store ------
