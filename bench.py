@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="rotating K/V copies (0 = enough to exceed 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bsp", action="store_true")
-    ap.add_argument("--no-waits", action="store_true", help="skip the fine-grained-waits variant (fd_decode_waits)")
+    ap.add_argument("--waits", action="store_true", help="also time the fine-grained-waits variant (fd_decode_waits)")
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only streaming kernel (achievable bandwidth)")
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
@@ -218,7 +218,7 @@ def main():
         bsp_ms, _ = time_calls(bsp, args.warmup, args.steps, torch)
 
     waits_ms = None
-    if not args.no_waits and not args.page_size and path == 2 and args.dtype == "bf16":
+    if args.waits and not args.page_size and path == 2 and args.dtype == "bf16":
         def waits(i):
             j = i % copies
             fd.fd_decode_waits(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)

@@ -145,7 +145,7 @@ int fd_decode_bsp(fd_handle_t h, const void* q, const void* k_cache, const void*
  * with events, so that `stream` sees one operation) waits per tile until the counter is
  * complete, then merges that tile, while other tiles are still being attended.  Kernel 1
  * never waits, so the counts always complete; the combine kernel's wait is bounded all the
- * same (FD_OPT_SPIN_LIMIT polls, ~0.2 us each): if it ever gives up, FD_INFO_WAIT_GAVE_UP
+ * same (FD_OPT_SPIN_LIMIT polls, ~1 us each): if it ever gives up, FD_INFO_WAIT_GAVE_UP
  * reads 1, out / lse of that call are undefined, and fd_reset is needed before the next
  * call.  MFMA kernel, contiguous cache only (else FD_ERR_UNSUPPORTED).
  */
@@ -208,7 +208,7 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
  *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto)
  *   FD_OPT_RING_STAGES   MFMA kernel: stages (16 keys of K and V, 8 KB) in each wave's
  *                        LDS ring: 0 auto (2), 2, 3 or 4; with 2 workgroups per CU always 2
- *   FD_OPT_SPIN_LIMIT    fd_decode_waits: polls before a waiting workgroup gives up (0 = 4194304)
+ *   FD_OPT_SPIN_LIMIT    fd_decode_waits: polls before a waiting workgroup gives up (0 = 1048576, about a second)
  *   FD_INFO_*            read-only, through fd_get_option; FD_INFO_WAIT_GAVE_UP synchronises the device
  */
 enum {

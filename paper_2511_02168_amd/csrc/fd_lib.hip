@@ -540,7 +540,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.part_lse = (float*)(ws + h->lay.part_lse_off);
     p.counters = (uint32_t*)(ws + h->lay.counters_off);
     p.status = (uint32_t*)(ws + h->lay.status_off);
-    p.spin_limit = h->opt_spin_limit > 0 ? (uint32_t)h->opt_spin_limit : (1u << 22);
+    p.spin_limit = h->opt_spin_limit > 0 ? (uint32_t)h->opt_spin_limit : (1u << 20);
     p.B = c.B; p.Hq = c.Hq; p.Hkv = c.Hkv; p.G = h->G; p.S_max = c.S_max;
     p.n_splits = n_splits;
     p.max_splits = c.max_splits;
