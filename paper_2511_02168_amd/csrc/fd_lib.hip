@@ -341,6 +341,9 @@ int check_config(const fd_config* c)
     const int G = c->Hq / c->Hkv;
     if (G > 16) return fail(FD_ERR_UNSUPPORTED, "GQA group Hq/Hkv = %d is not built (1..16)", G);
     if ((long long)c->B * c->Hkv > (1ll << 24)) return fail(FD_ERR_UNSUPPORTED, "B*Hkv too large");
+    // work items are counted in 32 bits
+    if ((long long)c->B * c->Hkv * c->max_splits >= (1ll << 31))
+        return fail(FD_ERR_UNSUPPORTED, "B*Hkv*max_splits = %lld does not fit 31 bits", (long long)c->B * c->Hkv * c->max_splits);
     return FD_OK;
 }
 

@@ -56,6 +56,7 @@ def test_workspace_bytes_formula():
     (dict(scale=float("nan")), fd.FD_ERR_INVALID_ARG),
     (dict(D=64), fd.FD_ERR_UNSUPPORTED),
     (dict(kv_layout=1), fd.FD_ERR_UNSUPPORTED),
+    (dict(B=1 << 20, Hq=16, Hkv=8, max_splits=1024), fd.FD_ERR_UNSUPPORTED),
     (dict(dtype=2), fd.FD_ERR_UNSUPPORTED),
     (dict(dtype=-1), fd.FD_ERR_UNSUPPORTED),
     (dict(Hq=68, Hkv=2), fd.FD_ERR_UNSUPPORTED),
