@@ -48,6 +48,12 @@ def _load():
         lib.fd_oracle_decode_fmt.argtypes = lib.fd_oracle_decode.argtypes + [ctypes.c_int]
         lib.fd_oracle_element.restype = ctypes.c_double
         lib.fd_oracle_element.argtypes = [ctypes.c_uint16, ctypes.c_int]
+        lib.fd_oracle_element_fp8.restype = ctypes.c_double
+        lib.fd_oracle_element_fp8.argtypes = [ctypes.c_uint8]
+        lib.fd_oracle_decode_fp8kv.restype = ctypes.c_int
+        lib.fd_oracle_decode_fp8kv.argtypes = [u16p, ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_uint8), i32p,
+                                               ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                               ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_int, f64p, f64p]
         lib.fd_oracle_partial.restype = ctypes.c_int
         lib.fd_oracle_partial.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_int64, ctypes.c_double,
@@ -183,3 +189,33 @@ def decode_paged(q: np.ndarray, k_pages: np.ndarray, v_pages: np.ndarray, block_
             k[b, :, j, :] = kp[page, :, j % page_size, :]
             v[b, :, j, :] = vp[page, :, j % page_size, :]
     return decode(q, k, v, sl.astype(np.int32), scale=scale, n_threads=n_threads, fmt=fmt)
+
+
+def element_fp8(bits: int) -> float:
+    """Exact value of one OCP E4M3 byte."""
+    return float(_load().fd_oracle_element_fp8(int(bits)))
+
+
+def decode_fp8kv(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lens: np.ndarray, k_scale: float = 1.0,
+                 v_scale: float = 1.0, scale: float = 0.0, n_threads: int = 0):
+    """Attention over an FP8 (E4M3) KV cache: q [B,Hq,D] bf16 bits (uint16); k, v [B,Hkv,S_max,D]
+    uint8 bytes standing for value * k_scale / v_scale.  Returns (out float64, lse float64)."""
+    q = _u16(q, 3, "q")
+    k = np.ascontiguousarray(k)
+    v = np.ascontiguousarray(v)
+    if k.dtype != np.uint8 or v.dtype != np.uint8 or k.ndim != 4 or k.shape != v.shape:
+        raise TypeError("k, v: expected equal-shaped uint8 arrays with 4 dims")
+    B, Hq, D = q.shape
+    if k.shape[0] != B or k.shape[3] != D:
+        raise ValueError("shape mismatch")
+    Hkv, S_max = k.shape[1], k.shape[2]
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    rc = _load().fd_oracle_decode_fp8kv(_ptr(q, ctypes.c_uint16), k.ctypes.data_as(u8p), v.ctypes.data_as(u8p),
+                                        _ptr(sl, ctypes.c_int32), B, Hq, Hkv, D, S_max, float(scale), float(k_scale),
+                                        float(v_scale), int(n_threads), _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("fd_oracle_decode_fp8kv rejected its arguments")
+    return out, lse

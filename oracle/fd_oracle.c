@@ -161,6 +161,88 @@ int fd_oracle_decode_fmt(const uint16_t* q, const uint16_t* k, const uint16_t* v
     return failed ? -1 : 0;
 }
 
+/*
+ * OCP FP8 E4M3 (the "fn" variant: 1 sign, 4 exponent bits with bias 7, 3 fraction bits; no
+ * infinities, 0x7f / 0xff are NaN, largest finite value 448) widened exactly.
+ */
+static double fp8_e4m3_to_double(uint8_t bits)
+{
+    const int sign = bits >> 7, e = (bits >> 3) & 15, f = bits & 7;
+    double mag;
+    if (e == 15 && f == 7) mag = NAN;
+    else if (e == 0) mag = ldexp((double)f, -9);
+    else mag = ldexp((double)(8 + f), e - 10);
+    return sign ? -mag : mag;
+}
+
+double fd_oracle_element_fp8(uint8_t bits) { return fp8_e4m3_to_double(bits); }
+
+/*
+ * Decode attention over an FP8 KV cache: q holds bf16 bit patterns, k and v hold E4M3
+ * bytes; a stored byte stands for value * k_scale (resp. v_scale), i.e.
+ *     s_j = scale * k_scale * <q, K8_j>,   out = v_scale * sum_j softmax(s)_j V8_j.
+ * Same two passes as attend_range, written out again because the element types differ.
+ */
+int fd_oracle_decode_fp8kv(const uint16_t* q, const uint8_t* k, const uint8_t* v,
+                           const int32_t* seq_lens, int B, int Hq, int Hkv, int D,
+                           int64_t S_max, double scale, double k_scale, double v_scale,
+                           int n_threads, double* out, double* lse)
+{
+    if (!q || !k || !v || !seq_lens || !out || !lse) return -1;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || S_max <= 0 || Hq % Hkv) return -1;
+    if (!(k_scale > 0.0) || !(v_scale > 0.0)) return -1;
+    for (int b = 0; b < B; ++b)
+        if (seq_lens[b] < 0 || seq_lens[b] > S_max) return -1;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)D);
+    const int G = Hq / Hkv;
+    int failed = 0;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#else
+    (void)n_threads;
+#endif
+#pragma omp parallel
+    {
+        double* scores = (double*)malloc(sizeof(double) * (size_t)S_max);
+        if (!scores) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int r = 0; r < B * Hq; ++r) {
+            if (!scores) continue;
+            const int b = r / Hq, h = r % Hq, kvh = h / G;
+            const uint16_t* qrow = q + (int64_t)r * D;
+            const uint8_t* kbase = k + ((int64_t)b * Hkv + kvh) * S_max * D;
+            const uint8_t* vbase = v + ((int64_t)b * Hkv + kvh) * S_max * D;
+            double* out_row = out + (int64_t)r * D;
+            const int64_t S = seq_lens[b];
+            for (int d = 0; d < D; ++d) out_row[d] = 0.0;
+            if (S == 0) {
+                lse[r] = -INFINITY;
+                continue;
+            }
+            double m = -INFINITY;
+            for (int64_t j = 0; j < S; ++j) {
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d) dot += bf16_bits_to_double(qrow[d]) * fp8_e4m3_to_double(kbase[j * D + d]);
+                scores[j] = scale * k_scale * dot;
+                if (scores[j] > m) m = scores[j];
+            }
+            double l = 0.0;
+            for (int64_t j = 0; j < S; ++j) l += exp(scores[j] - m);
+            for (int64_t j = 0; j < S; ++j) {
+                const double w = exp(scores[j] - m) / l;
+                for (int d = 0; d < D; ++d) out_row[d] += w * fp8_e4m3_to_double(vbase[j * D + d]);
+            }
+            for (int d = 0; d < D; ++d) out_row[d] *= v_scale;
+            lse[r] = m + log(l);
+        }
+        free(scores);
+    }
+    return failed ? -1 : 0;
+}
+
 /* The same for bf16 bit patterns (the benchmark's format). */
 int fd_oracle_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                      const int32_t* seq_lens, int B, int Hq, int Hkv, int D,

@@ -497,3 +497,40 @@ def test_fp16_decode_equals_fp64_reference_on_the_widened_values():
         ref = torch.einsum("hj,hjd->hd", torch.softmax(s, -1), vt).numpy()
         assert np.allclose(o[b], ref, rtol=1e-12, atol=1e-13)
         assert np.allclose(l[b], torch.logsumexp(s, -1).numpy(), rtol=1e-12, atol=1e-13)
+
+
+# ---- FP8 (E4M3) KV cache ------------------------------------------------------------------
+
+def test_fp8_e4m3_widening_matches_torch_and_fixed_patterns():
+    for bits, val in ((0x38, 1.0), (0x7E, 448.0), (0x01, 2.0 ** -9), (0x08, 2.0 ** -6), (0xC0, -2.0), (0x3C, 1.5), (0x00, 0.0)):
+        assert oracle.element_fp8(bits) == val
+    assert math.isnan(oracle.element_fp8(0x7F)) and math.isnan(oracle.element_fp8(0xFF))
+    allb = torch.arange(256, dtype=torch.int32).to(torch.uint8)
+    ref = allb.view(torch.float8_e4m3fn).to(torch.float64).numpy()          # torch's own decoder
+    got = np.array([oracle.element_fp8(b) for b in range(256)])
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], ref[~nan])
+
+
+def test_fp8kv_decode_equals_bf16_decode_on_fp8_representable_values():
+    """Every E4M3 value is a bf16 value: feeding the bf16 oracle the same numbers must give the same result
+    (scales 1), and the scales act as plain factors on the scores and on the output."""
+    rng = np.random.default_rng(31)
+    B, Hq, Hkv, S, D = 2, 4, 2, 29, 16
+    kb = rng.integers(0, 256, (B, Hkv, S, D)).astype(np.uint8)
+    vb = rng.integers(0, 256, (B, Hkv, S, D)).astype(np.uint8)
+    kb[(kb & 0x7F) == 0x7F] = 0x38                                           # no NaN patterns
+    vb[(vb & 0x7F) == 0x7F] = 0x38
+    kb = np.where((kb & 0x78) > 0x48, (kb & 0x87) | 0x30, kb).astype(np.uint8)   # keep |K| small: no overflowing scores
+    q = f32_to_bf16_bits(rng.standard_normal((B, Hq, D)).astype(np.float32))
+    sl = np.array([S, 11], dtype=np.int32)
+    dec = np.vectorize(oracle.element_fp8)
+    k16 = f32_to_bf16_bits(dec(kb).astype(np.float32))
+    v16 = f32_to_bf16_bits(dec(vb).astype(np.float32))
+    assert np.array_equal(bf16_bits_to_f32(k16).astype(np.float64), dec(kb))          # exactly representable
+    o_ref, l_ref = oracle.decode(q, k16, v16, sl)
+    o, l = oracle.decode_fp8kv(q, kb, vb, sl)
+    assert np.allclose(o, o_ref, rtol=1e-13, atol=1e-15) and np.allclose(l, l_ref, rtol=1e-13, atol=1e-13)
+    o2, l2 = oracle.decode_fp8kv(q, kb, vb, sl, k_scale=0.5, v_scale=3.0)
+    o3, l3 = oracle.decode(q, k16, v16, sl, scale=0.5 / math.sqrt(D))
+    assert np.allclose(o2, 3.0 * o3, rtol=1e-13, atol=1e-15) and np.allclose(l2, l3, rtol=1e-13, atol=1e-13)
