@@ -43,7 +43,8 @@ def parse_args():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
     ap.add_argument("--ring-stages", type=int, default=0)
-    ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16"], help="element type of q/K/V (fp16 = the paper's)")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16", "fp8kv"],
+                    help="element type of q/K/V (fp16 = the paper's; fp8kv = bf16 q over an E4M3 cache, scales 1/32)")
     ap.add_argument("--autotune", action="store_true",
                     help="let fd_autotune pick the options for this shape first (untimed); the choice is reported")
     ap.add_argument("--page-size", type=int, default=0,
@@ -157,14 +158,18 @@ def main():
     wl = fi.workload(args.config)
     inp = fi.make_inputs(wl, "cuda", dtype=torch.float16 if args.dtype == "fp16" else torch.bfloat16)
     sl_host = inp.seq_lens.cpu().numpy()
-    alg_bytes = fi.algorithmic_bytes(wl, sl_host)
-    kv_bytes = inp.k.numel() * 2 * 2
+    fp8 = args.dtype == "fp8kv"
+    if fp8:
+        inp.k, inp.v = fi.to_fp8_cache(inp)
+    alg_bytes = fi.algorithmic_bytes(wl, sl_host, 1 if fp8 else 2)
+    kv_bytes = inp.k.numel() * inp.k.element_size() * 2
     copies = args.copies or max(2, -(-(1 << 30) // kv_bytes) + 1)
     copies = min(copies, 64)
     ks = [inp.k] + [inp.k.clone() for _ in range(copies - 1)]
     vs = [inp.v] + [inp.v.clone() for _ in range(copies - 1)]
     max_splits = wl.n_splits if wl.n_splits > 0 else -(-wl.S_max // 512)
-    dec = fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max_splits, dtype=args.dtype)
+    dec = fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max_splits, dtype=args.dtype,
+                         k_scale=1.0 / 32 if fp8 else 0.0, v_scale=1.0 / 32 if fp8 else 0.0)
     for key, val in ((fd.FD_OPT_XCD_GROUPS, args.xcd_groups), (fd.FD_OPT_WGS_PER_CU, args.wgs_per_cu),
                      (fd.FD_OPT_PATH, args.path), (fd.FD_OPT_RING_STAGES, args.ring_stages)):
         if val:
@@ -263,7 +268,7 @@ def main():
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
                      "kernel": "fd fused persistent kernel (one launch per call)"},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not fp8:
         rec["cpu_baseline"] = cpu_baseline(inp, wl, fi, args.dtype)
     dec.close()
     print(json.dumps(rec))

@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define FD_VERSION 120
+#define FD_VERSION 130
 
 enum {
     FD_OK = 0,
@@ -71,6 +71,13 @@ typedef struct fd_handle_s* fd_handle_t;
  *               paper's format, Section 5.1): wherever the comments below say bf16, read
  *               "dtype".  Half inputs run on the MFMA kernel only (FD_OPT_PATH = 1 and
  *               fd_decode_waits are FD_ERR_UNSUPPORTED); sums are fp32 either way.
+ *               FD_DTYPE_FP8_KV: q is bf16, k_cache and v_cache hold ONE BYTE per element,
+ *               OCP FP8 E4M3 (largest value 448, 0x7f / 0xff = NaN), same [B, Hkv, S_max, D]
+ *               shape; a byte stands for value * k_scale (v_scale):
+ *               out = v_scale * softmax(scale * k_scale * q K8^T) V8.  Half the cache
+ *               bytes per key.  MFMA kernel, contiguous layout, fd_decode / fd_decode_bsp.
+ *   k_scale,    per-tensor dequantisation factors of an FP8 cache (0 means 1); ignored for
+ *   v_scale     the other dtypes
  */
 typedef struct {
     int32_t B, Hq, Hkv, D, S_max;
@@ -78,11 +85,13 @@ typedef struct {
     int32_t kv_layout;
     float scale;
     int32_t dtype;
+    float k_scale, v_scale;
 } fd_config;
 
 /* fd_config.dtype: element type of q, k_cache, v_cache (out and lse are always fp32). */
 #define FD_DTYPE_BF16 0
 #define FD_DTYPE_FP16 1
+#define FD_DTYPE_FP8_KV 2
 
 /* Bytes of device workspace fd_create() allocates for cfg (0 if cfg is invalid). */
 size_t fd_workspace_bytes(const fd_config* cfg);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libfd.so")
 
 FD_OK, FD_ERR_INVALID_ARG, FD_ERR_UNSUPPORTED, FD_ERR_WORKSPACE, FD_ERR_HIP = 0, -1, -2, -3, -4
 FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES, FD_OPT_SPIN_LIMIT = 1, 2, 3, 4, 5
-FD_DTYPE_BF16, FD_DTYPE_FP16 = 0, 1
+FD_DTYPE_BF16, FD_DTYPE_FP16, FD_DTYPE_FP8_KV = 0, 1, 2
 FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH, FD_INFO_WAIT_GAVE_UP = 100, 101, 102, 103
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
@@ -29,7 +29,8 @@ EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_deco
 class fd_config(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("S_max", ctypes.c_int32), ("max_splits", ctypes.c_int32),
-                ("kv_layout", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
+                ("kv_layout", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32),
+                ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 class FdError(RuntimeError):
@@ -191,8 +192,9 @@ class FlashDecode:
     """Convenience owner of one handle: shapes fixed at construction."""
 
     def __init__(self, B: int, Hq: int, Hkv: int, S_max: int, max_splits: int = 256, D: int = 128,
-                 scale: float = 0.0, dtype: str = "bf16"):
-        self.cfg = fd_config(B, Hq, Hkv, D, S_max, max_splits, 0, scale, {"bf16": FD_DTYPE_BF16, "fp16": FD_DTYPE_FP16}[dtype])
+                 scale: float = 0.0, dtype: str = "bf16", k_scale: float = 0.0, v_scale: float = 0.0):
+        code = {"bf16": FD_DTYPE_BF16, "fp16": FD_DTYPE_FP16, "fp8kv": FD_DTYPE_FP8_KV}[dtype]
+        self.cfg = fd_config(B, Hq, Hkv, D, S_max, max_splits, 0, scale, code, k_scale, v_scale)
         self.h = fd_create(self.cfg)
 
     def close(self) -> None:
@@ -217,7 +219,8 @@ class FlashDecode:
         c = self.cfg
         assert q.is_cuda and k.is_cuda and v.is_cuda and seq_lens.is_cuda and out.is_cuda
         want = torch.float16 if c.dtype == FD_DTYPE_FP16 else torch.bfloat16
-        assert q.dtype == want and k.dtype == want and v.dtype == want
+        want_kv = torch.float8_e4m3fn if c.dtype == FD_DTYPE_FP8_KV else want
+        assert q.dtype == want and k.dtype == want_kv and v.dtype == want_kv
         assert seq_lens.dtype == torch.int32 and out.dtype == torch.float32
         assert tuple(q.shape) == (c.B, c.Hq, c.D) and q.is_contiguous()
         assert tuple(k.shape) == (c.B, c.Hkv, c.S_max, c.D) and k.is_contiguous()

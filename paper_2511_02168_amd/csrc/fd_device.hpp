@@ -45,7 +45,8 @@ struct Params {
     int32_t n_splits;         // 0 = adaptive
     int32_t max_splits;
     int32_t xcd_groups;       // 1 or 8
-    float scale_log2;         // softmax scale * log2(e)
+    float scale_log2;         // softmax scale * log2(e) (FP8 cache: times k_scale)
+    float out_mul;            // factor on every normalised output row: 1, or v_scale of an FP8 cache
     unsigned long long* trace;  // optional [grid][kTraceEvents] timestamps (100 MHz), or null
 };
 
@@ -272,7 +273,8 @@ struct ItemSmem {
 // returns with every thread past its last read of sm.  A thread produces 4 dims of
 // one head: this tail runs with one wave per SIMD, where every instruction counts.
 template <int ROWS, bool SHARED>
-__device__ inline void item_finish(const ItemSmem<ROWS>& sm, int G, float* dst_o, float* dst_lse, float lse_mul)
+__device__ inline void item_finish(const ItemSmem<ROWS>& sm, int G, float* dst_o, float* dst_lse, float lse_mul,
+                                   float out_mul = 1.0f)
 {
     static_assert(kWaves == 4, "the wave states of a head are read as one float4");
 #pragma nounroll
@@ -292,7 +294,7 @@ __device__ inline void item_finish(const ItemSmem<ROWS>& sm, int G, float* dst_o
             o[2] += a.z * f[w];
             o[3] += a.w * f[w];
         }
-        o *= __builtin_amdgcn_rcpf(L);
+        o *= __builtin_amdgcn_rcpf(L) * out_mul;
         const float res_lse = (M + fast_log2(L)) * lse_mul;
         if (SHARED) {
             store_agent4(&dst_o[4 * idx], o);

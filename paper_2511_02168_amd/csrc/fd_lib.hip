@@ -14,6 +14,7 @@
 #include "fd_device.hpp"
 #include "fd_valu.hpp"
 #include "fd_mfma.hpp"
+#include "fd_mfma8.hpp"
 
 namespace fd {
 
@@ -42,6 +43,17 @@ struct MfmaPath {
                                          float mul) const
     {
         mfma_item<NST, PAGED, F16, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+    }
+};
+
+template <int NST>
+struct Mfma8Path {
+    char* ring;
+    template <bool SHARED>
+    __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
+                                         float mul) const
+    {
+        mfma8_item<NST, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
     }
 };
 
@@ -175,6 +187,15 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
     static_assert(sizeof(CombineSmem) <= (size_t)mfma_ring_bytes(NST), "combine scratch must fit the ring");
     __shared__ SchedSmem ss;
     persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, MfmaPath<NST, PAGED, F16>{fd_dyn_smem}, ss,
+                                                        *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
+}
+
+// The MFMA kernel over an FP8 (E4M3) KV cache: 32-key stages converted to bf16 between LDS and the matrix cores.
+template <bool FUSED, int CB>
+__global__ __launch_bounds__(kWgThreads, 1) void fd_mfma8_kernel(Params p)
+{
+    __shared__ SchedSmem ss;
+    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, Mfma8Path<2>{fd_dyn_smem}, ss,
                                                         *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
@@ -336,8 +357,10 @@ int check_config(const fd_config* c)
     if (!(c->scale >= 0.0f) || std::isinf(c->scale)) return fail(FD_ERR_INVALID_ARG, "scale must be finite and >= 0");
     if (c->D != fd::kD) return fail(FD_ERR_UNSUPPORTED, "only D = 128 is built (got %d)", c->D);
     if (c->kv_layout != 0) return fail(FD_ERR_UNSUPPORTED, "only kv_layout 0 ([B,Hkv,S_max,D]) is built");
-    if (c->dtype != FD_DTYPE_BF16 && c->dtype != FD_DTYPE_FP16)
-        return fail(FD_ERR_UNSUPPORTED, "dtype must be FD_DTYPE_BF16 (0) or FD_DTYPE_FP16 (1), got %d", c->dtype);
+    if (c->dtype != FD_DTYPE_BF16 && c->dtype != FD_DTYPE_FP16 && c->dtype != FD_DTYPE_FP8_KV)
+        return fail(FD_ERR_UNSUPPORTED, "dtype must be FD_DTYPE_BF16 (0), FD_DTYPE_FP16 (1) or FD_DTYPE_FP8_KV (2), got %d", c->dtype);
+    if (!(c->k_scale >= 0.0f) || !(c->v_scale >= 0.0f) || std::isinf(c->k_scale) || std::isinf(c->v_scale))
+        return fail(FD_ERR_INVALID_ARG, "k_scale and v_scale must be finite and >= 0");
     const int G = c->Hq / c->Hkv;
     if (G > 16) return fail(FD_ERR_UNSUPPORTED, "GQA group Hq/Hkv = %d is not built (1..16)", G);
     if ((long long)c->B * c->Hkv > (1ll << 24)) return fail(FD_ERR_UNSUPPORTED, "B*Hkv too large");
@@ -422,6 +445,30 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
+template <int CB>
+int launch_mfma8(const fd::Params& p, bool fused, int grid, hipStream_t st)
+{
+    static thread_local int granted_device[2] = {-1, -1};
+    int dev = 0;
+    FD_HIP(hipGetDevice(&dev));
+    const size_t lds = (size_t)fd::mfma_lds_bytes(2);
+    if (granted_device[fused] != dev) {
+        if (fused)
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<true, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        else
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<false, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        granted_device[fused] = dev;
+    }
+    if (fused) {
+        hipLaunchKernelGGL((fd::fd_mfma8_kernel<true, CB>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+        FD_HIP(hipGetLastError());
+        return FD_OK;
+    }
+    hipLaunchKernelGGL((fd::fd_mfma8_kernel<false, CB>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+    FD_HIP(hipGetLastError());
+    return launch_combine(p, st);
+}
+
 // Fine-grained waits (Section 4.2.4): kernel 1 (partials + arrival counts) on the caller's
 // stream, the waiting combine kernel on the handle's second stream, forked and joined with
 // events so that the caller's stream sees one operation.  Kernel 1 goes first: if the
@@ -493,6 +540,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         if (path == 1) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel does not read paged caches");
         path = 2;
     }
+    if (c.dtype == FD_DTYPE_FP8_KV) {
+        if (path == 1 || pg.table || mode == fd::kModeSignal)
+            return fail(FD_ERR_UNSUPPORTED, "an FP8 cache is read by the MFMA kernel, contiguous layout, fused or BSP only");
+        path = 2;
+    }
     if (c.dtype == FD_DTYPE_FP16) {
         if (path == 1) return fail(FD_ERR_UNSUPPORTED, "the VALU kernel is built for bf16 only");
         if (mode == fd::kModeSignal) return fail(FD_ERR_UNSUPPORTED, "the fine-grained-waits variant is built for bf16 only");
@@ -550,6 +602,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.xcd_groups = X;
     const float scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.D);
     p.scale_log2 = scale * 1.4426950408889634f;
+    p.out_mul = 1.0f;
+    if (c.dtype == FD_DTYPE_FP8_KV) {
+        p.scale_log2 *= c.k_scale > 0.f ? c.k_scale : 1.0f;
+        p.out_mul = c.v_scale > 0.f ? c.v_scale : 1.0f;
+    }
     p.trace = (h->trace && grid <= h->trace_capacity) ? h->trace : nullptr;
 
     hipStream_t st = (hipStream_t)stream;
@@ -560,6 +617,8 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         int nst = h->opt_ring > 0 ? h->opt_ring : 2;
         if (per_cu > 1) nst = 2;                       // two workgroups per CU share the LDS
         const bool two = per_cu > 1;
+        if (h->cfg.dtype == FD_DTYPE_FP8_KV)
+            return two ? launch_mfma8<8>(p, fused, (int)grid, st) : launch_mfma8<32>(p, fused, (int)grid, st);
         if (h->cfg.dtype == FD_DTYPE_FP16) {           // the half and the paged kernels are built for the default ring depth
             if (pg.table)
                 return two ? launch_mfma<2, 8, true, true>(p, fused, (int)grid, st)

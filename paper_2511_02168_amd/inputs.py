@@ -79,6 +79,19 @@ class Inputs:
     wl: Workload = field(repr=False, default=None)
 
 
+def to_fp8_cache(inp: "Inputs", k_scale: float = 1.0 / 32, v_scale: float = 1.0 / 32):
+    """K and V of a bf16 workload quantised to OCP E4M3 bytes standing for value * scale: returns (k8, v8) as
+    torch.float8_e4m3fn tensors of the same shape (NaN padding stays NaN).  N(0,1) / (1/32) stays far below 448."""
+    k8 = (inp.k.to(torch.float32) / k_scale).to(torch.float8_e4m3fn)
+    v8 = (inp.v.to(torch.float32) / v_scale).to(torch.float8_e4m3fn)
+    return k8, v8
+
+
+def bytes_of(t: torch.Tensor) -> np.ndarray:
+    """Raw bytes of an 8-bit tensor as a host uint8 array."""
+    return t.contiguous().view(torch.uint8).cpu().numpy()
+
+
 def bits(t: torch.Tensor) -> np.ndarray:
     """Exact bit patterns of a bf16 (or fp16) tensor as a host uint16 array."""
     assert t.dtype in (torch.bfloat16, torch.float16)
@@ -207,11 +220,11 @@ def make_paged(inp: Inputs, page_size: int, seed: int = 0) -> PagedInputs:
                        seq_lens=inp.seq_lens, page_size=page_size)
 
 
-def algorithmic_bytes(wl: Workload, seq_lens) -> int:
+def algorithmic_bytes(wl: Workload, seq_lens, kv_elem_bytes: int = 2) -> int:
     """Bytes the method must move: K and V rows of every live key once, q in, out + lse out."""
     lens = [int(s) for s in seq_lens]
     B = len(lens)
-    kv = sum(lens) * wl.Hkv * wl.D * 2 * 2
+    kv = sum(lens) * wl.Hkv * wl.D * kv_elem_bytes * 2
     return kv + B * wl.Hq * wl.D * 2 + B * wl.Hq * wl.D * 4 + B * wl.Hq * 4
 
 

@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_is_built_and_loads():
     assert os.path.exists(fd.LIB_PATH), "run `python -m paper_2511_02168_amd.build` first"
-    assert fd.fd_version() == 120
+    assert fd.fd_version() == 130
 
 
 def test_every_declared_symbol_is_exported():
@@ -33,9 +33,9 @@ def test_every_declared_symbol_is_exported():
 
 
 def good_cfg(**kw):
-    base = dict(B=2, Hq=8, Hkv=2, D=128, S_max=4096, max_splits=16, kv_layout=0, scale=0.0, dtype=0)
+    base = dict(B=2, Hq=8, Hkv=2, D=128, S_max=4096, max_splits=16, kv_layout=0, scale=0.0, dtype=0, k_scale=0.0, v_scale=0.0)
     base.update(kw)
-    return fd.fd_config(*[base[k] for k in ("B", "Hq", "Hkv", "D", "S_max", "max_splits", "kv_layout", "scale", "dtype")])
+    return fd.fd_config(*[base[k] for k in ("B", "Hq", "Hkv", "D", "S_max", "max_splits", "kv_layout", "scale", "dtype", "k_scale", "v_scale")])
 
 
 def test_workspace_bytes_formula():
@@ -57,7 +57,8 @@ def test_workspace_bytes_formula():
     (dict(D=64), fd.FD_ERR_UNSUPPORTED),
     (dict(kv_layout=1), fd.FD_ERR_UNSUPPORTED),
     (dict(B=1 << 20, Hq=16, Hkv=8, max_splits=1024), fd.FD_ERR_UNSUPPORTED),
-    (dict(dtype=2), fd.FD_ERR_UNSUPPORTED),
+    (dict(dtype=3), fd.FD_ERR_UNSUPPORTED),
+    (dict(dtype=2, k_scale=-1.0), fd.FD_ERR_INVALID_ARG),
     (dict(dtype=-1), fd.FD_ERR_UNSUPPORTED),
     (dict(Hq=68, Hkv=2), fd.FD_ERR_UNSUPPORTED),
 ])

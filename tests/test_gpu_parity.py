@@ -659,3 +659,60 @@ def test_half_inputs_peaked_attention():
         out, lse = run_both(dec, inp, 16)
     check_out(out, ref_o, "half peaked")
     check_lse(lse, ref_l, "half peaked")
+
+
+# ---------------------------------------------------------------- FP8 (E4M3) KV cache
+
+@pytest.mark.parametrize("shape", [(2, 8, 8, 1000, 4), (3, 16, 2, 2500, 0), (2, 12, 4, 777, 3), (1, 16, 1, 30000, 37),
+                                   (2, 32, 2, 513, 0), (1, 8, 1, 31, 1), (1, 8, 1, 33, 2), (4, 4, 4, 64, 0)])
+def test_fp8_kv_cache(shape):
+    """dtype = FD_DTYPE_FP8_KV: bf16 q, E4M3 K/V bytes with per-tensor scales.  The oracle reads the same bytes;
+    the kernel converts them exactly, so the tolerances are the bf16 ones."""
+    B, Hq, Hkv, S, n = shape
+    wl = _generic(B, Hq, Hkv, S, 1400 + S + Hq, ragged=(n == 0))
+    say(f"case FP8 KV cache B{B} Hq{Hq} Hkv{Hkv} S{S} n{n}")
+    inp = fi.make_inputs(wl, "cuda")
+    ks, vs = 1.0 / 32, 1.0 / 16
+    k8, v8 = fi.to_fp8_cache(inp, ks, vs)
+    ref_o, ref_l = oracle.decode_fp8kv(fi.bits(inp.q), fi.bytes_of(k8), fi.bytes_of(v8), inp.seq_lens.cpu().numpy(),
+                                       k_scale=ks, v_scale=vs)
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=max(n, 8), dtype="fp8kv", k_scale=ks, v_scale=vs) as dec:
+        fd.fd_debug_poison_workspace(dec.h)
+        out_f, lse_f = dec.decode(inp.q, k8, v8, inp.seq_lens, n)
+        out_b, lse_b = dec.decode(inp.q, k8, v8, inp.seq_lens, n, bsp=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out_f.view(torch.int32), out_b.view(torch.int32)) and torch.equal(lse_f, lse_b)
+        eo = check_out(out_f.cpu().numpy(), ref_o, "fp8 kv")
+        el = check_lse(lse_f.cpu().numpy(), ref_l, "fp8 kv")
+        say(f"  max |out err| {eo:.2e}, max |lse err| {el:.2e}")
+        fd.fd_set_option(dec.h, fd.FD_OPT_WGS_PER_CU, 2)
+        out_2, lse_2 = dec.decode(inp.q, k8, v8, inp.seq_lens, n)
+        torch.cuda.synchronize()
+        check_out(out_2.cpu().numpy(), ref_o, "fp8 kv, 2 per CU")
+        fd.fd_set_option(dec.h, fd.FD_OPT_WGS_PER_CU, 0)
+        with pytest.raises(fd.FdError) as e:
+            dec.decode(inp.q, k8, v8, inp.seq_lens, n, waits=True)
+        assert e.value.code == fd.FD_ERR_UNSUPPORTED
+
+
+def test_fp8_kv_cache_every_byte_value():
+    """A cache holding every finite E4M3 byte (both signs, subnormals, the 448 maximum) with tiny scales."""
+    wl = _generic(1, 8, 1, 512, 1500)
+    inp = fi.make_inputs(wl, "cuda")
+    allb = torch.arange(256, dtype=torch.int32).to(torch.uint8)
+    allb[allb == 0x7F] = 0x7E
+    allb[allb == 0xFF] = 0xFE
+    gen = torch.Generator().manual_seed(3)
+    kb = allb[torch.randint(0, 256, (1, 1, 512, 128), generator=gen)].cuda()
+    vb = allb[torch.randint(0, 256, (1, 1, 512, 128), generator=gen)].cuda()
+    k8, v8 = kb.view(torch.float8_e4m3fn), vb.view(torch.float8_e4m3fn)
+    ks, vs = 1.0 / 4096, 1.0 / 8
+    ref_o, ref_l = oracle.decode_fp8kv(fi.bits(inp.q), fi.bytes_of(k8), fi.bytes_of(v8), inp.seq_lens.cpu().numpy(),
+                                       k_scale=ks, v_scale=vs)
+    with fd.FlashDecode(1, 8, 1, 512, max_splits=8, dtype="fp8kv", k_scale=ks, v_scale=vs) as dec:
+        out, lse = dec.decode(inp.q, k8, v8, inp.seq_lens, 4)
+        torch.cuda.synchronize()
+    ref_scale = np.abs(ref_o).max()
+    say(f"case FP8 every byte value: |out| up to {ref_scale:.2f}")
+    check_out(out.cpu().numpy(), ref_o, "fp8 all bytes")
+    check_lse(lse.cpu().numpy(), ref_l, "fp8 all bytes")
