@@ -70,10 +70,11 @@ constexpr int kModeBsp = 0, kModeFused = 1, kModeSignal = 2;
 // Counter value of a tile whose result kernel 1 wrote itself (fine-grained waits).
 constexpr uint32_t kTileDirect = 0x80000000u;
 
-// The persistent loop of a workgroup.  FUSED: steps a1-a8 in one launch (the
-// workgroup that completes a tile's split count merges the tile: paper Section
-// 4.2.5 / Algorithm 4 without the barrier and without the second launch).
-// !FUSED: steps a1-a6 only (kernel 1 of the bulk-synchronous baseline, Section 4.2.2).
+// The persistent loop of a workgroup.  kModeFused: work decomposition to combine in one
+// launch (the workgroup that completes a tile's split count merges the tile: paper Section
+// 4.2.5 / Algorithm 4 without the barrier and without the second launch).  kModeBsp: up to
+// the partial only (kernel 1 of the bulk-synchronous baseline, Section 4.2.2).  kModeSignal:
+// partial and arrival count (kernel 1 of the fine-grained-waits variant, Section 4.2.4).
 template <int MODE, int COMB_BATCH, class Path>
 __device__ __forceinline__ void persistent_loop(const Params& p, const Path& path, SchedSmem& ss, CombineSmem& comb)
 {
