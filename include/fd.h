@@ -75,7 +75,8 @@ typedef struct fd_handle_s* fd_handle_t;
  *               OCP FP8 E4M3 (largest value 448, 0x7f / 0xff = NaN), same [B, Hkv, S_max, D]
  *               shape; a byte stands for value * k_scale (v_scale):
  *               out = v_scale * softmax(scale * k_scale * q K8^T) V8.  Half the cache
- *               bytes per key.  MFMA kernel, contiguous layout, fd_decode / fd_decode_bsp.
+ *               bytes per key.  MFMA kernel; fd_decode / fd_decode_bsp, and the paged entry
+ *               points with pages of at least 32 keys (pool of bytes, same shape).
  *   k_scale,    per-tensor dequantisation factors of an FP8 cache (0 means 1); ignored for
  *   v_scale     the other dtypes
  */

@@ -219,3 +219,28 @@ def decode_fp8kv(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lens: np.ndarr
     if rc != 0:
         raise ValueError("fd_oracle_decode_fp8kv rejected its arguments")
     return out, lse
+
+
+def decode_fp8kv_paged(q: np.ndarray, k_pages: np.ndarray, v_pages: np.ndarray, block_table: np.ndarray,
+                       seq_lens: np.ndarray, k_scale: float = 1.0, v_scale: float = 1.0, scale: float = 0.0):
+    """decode_fp8kv over a paged cache (uint8 pools [num_pages,Hkv,page_size,D]), by the same
+    row-by-row gather as decode_paged."""
+    q = _u16(q, 3, "q")
+    kp, vp = np.ascontiguousarray(k_pages), np.ascontiguousarray(v_pages)
+    if kp.dtype != np.uint8 or vp.dtype != np.uint8 or kp.ndim != 4 or kp.shape != vp.shape:
+        raise TypeError("k_pages, v_pages: expected equal-shaped uint8 arrays with 4 dims")
+    num_pages, Hkv, page_size, D = kp.shape
+    B = q.shape[0]
+    bt = np.asarray(block_table)
+    sl = np.asarray(seq_lens, dtype=np.int64)
+    S_max = max(1, int(sl.max()) if B else 1)
+    k = np.zeros((B, Hkv, S_max, D), dtype=np.uint8)
+    v = np.zeros((B, Hkv, S_max, D), dtype=np.uint8)
+    for b in range(B):
+        for j in range(int(sl[b])):
+            page = int(bt[b, j // page_size])
+            if not 0 <= page < num_pages:
+                raise ValueError(f"block_table[{b}, {j // page_size}] = {page} is not a page")
+            k[b, :, j, :] = kp[page, :, j % page_size, :]
+            v[b, :, j, :] = vp[page, :, j % page_size, :]
+    return decode_fp8kv(q, k, v, sl.astype(np.int32), k_scale=k_scale, v_scale=v_scale, scale=scale)

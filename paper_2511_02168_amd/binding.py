@@ -255,7 +255,8 @@ class FlashDecode:
             lse = torch.empty(c.B, c.Hq, device=q.device, dtype=torch.float32)
         assert k_pages.is_cuda and v_pages.is_cuda and block_table.is_cuda and q.is_cuda and seq_lens.is_cuda
         want = torch.float16 if c.dtype == FD_DTYPE_FP16 else torch.bfloat16
-        assert k_pages.dtype == want and v_pages.dtype == want and block_table.dtype == torch.int32
+        want_kv = torch.float8_e4m3fn if c.dtype == FD_DTYPE_FP8_KV else want
+        assert k_pages.dtype == want_kv and v_pages.dtype == want_kv and block_table.dtype == torch.int32
         assert k_pages.shape == v_pages.shape and k_pages.is_contiguous() and v_pages.is_contiguous()
         assert tuple(k_pages.shape[1:]) == (c.Hkv, page_size, c.D)
         assert block_table.dim() == 2 and block_table.shape[0] == c.B and block_table.is_contiguous()

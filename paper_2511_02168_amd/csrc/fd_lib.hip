@@ -46,14 +46,14 @@ struct MfmaPath {
     }
 };
 
-template <int NST>
+template <int NST, bool PAGED>
 struct Mfma8Path {
     char* ring;
     template <bool SHARED>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
                                          float mul) const
     {
-        mfma8_item<NST, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+        mfma8_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
     }
 };
 
@@ -192,11 +192,11 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 }
 
 // The MFMA kernel over an FP8 (E4M3) KV cache: 32-key stages converted to bf16 between LDS and the matrix cores.
-template <bool FUSED, int CB>
+template <bool FUSED, int CB, bool PAGED>
 __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma8_kernel(Params p)
 {
     __shared__ SchedSmem ss;
-    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, Mfma8Path<2>{fd_dyn_smem}, ss,
+    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, Mfma8Path<2, PAGED>{fd_dyn_smem}, ss,
                                                         *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
@@ -446,7 +446,7 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
-template <int CB>
+template <int CB, bool PAGED>
 int launch_mfma8(const fd::Params& p, bool fused, int grid, hipStream_t st)
 {
     static thread_local int granted_device[2] = {-1, -1};
@@ -455,17 +455,17 @@ int launch_mfma8(const fd::Params& p, bool fused, int grid, hipStream_t st)
     const size_t lds = (size_t)fd::mfma_lds_bytes(2);
     if (granted_device[fused] != dev) {
         if (fused)
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<true, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<true, CB, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         else
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<false, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<false, CB, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         granted_device[fused] = dev;
     }
     if (fused) {
-        hipLaunchKernelGGL((fd::fd_mfma8_kernel<true, CB>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+        hipLaunchKernelGGL((fd::fd_mfma8_kernel<true, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
         FD_HIP(hipGetLastError());
         return FD_OK;
     }
-    hipLaunchKernelGGL((fd::fd_mfma8_kernel<false, CB>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+    hipLaunchKernelGGL((fd::fd_mfma8_kernel<false, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
     FD_HIP(hipGetLastError());
     return launch_combine(p, st);
 }
@@ -542,8 +542,10 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         path = 2;
     }
     if (c.dtype == FD_DTYPE_FP8_KV) {
-        if (path == 1 || pg.table || mode == fd::kModeSignal)
-            return fail(FD_ERR_UNSUPPORTED, "an FP8 cache is read by the MFMA kernel, contiguous layout, fused or BSP only");
+        if (path == 1 || mode == fd::kModeSignal)
+            return fail(FD_ERR_UNSUPPORTED, "an FP8 cache is read by the MFMA kernel, fused or BSP only");
+        if (pg.table && pg.page_size < 32)
+            return fail(FD_ERR_UNSUPPORTED, "an FP8 cache is paged in pages of at least 32 keys (got %d)", pg.page_size);
         path = 2;
     }
     if (c.dtype == FD_DTYPE_FP16) {
@@ -619,7 +621,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         if (per_cu > 1) nst = 2;                       // two workgroups per CU share the LDS
         const bool two = per_cu > 1;
         if (h->cfg.dtype == FD_DTYPE_FP8_KV)
-            return two ? launch_mfma8<8>(p, fused, (int)grid, st) : launch_mfma8<32>(p, fused, (int)grid, st);
+        {
+            if (pg.table)
+                return two ? launch_mfma8<8, true>(p, fused, (int)grid, st) : launch_mfma8<32, true>(p, fused, (int)grid, st);
+            return two ? launch_mfma8<8, false>(p, fused, (int)grid, st) : launch_mfma8<32, false>(p, fused, (int)grid, st);
+        }
         if (h->cfg.dtype == FD_DTYPE_FP16) {           // the half and the paged kernels are built for the default ring depth
             if (pg.table)
                 return two ? launch_mfma<2, 8, true, true>(p, fused, (int)grid, st)

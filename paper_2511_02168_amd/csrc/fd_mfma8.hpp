@@ -139,8 +139,9 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
     }
 }
 
-// Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) of an FP8 cache; contract as mfma_item.
-template <int NST, bool SHARED>
+// Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) of an FP8 cache; contract as mfma_item,
+// PAGED as there (a 32-key block never straddles a page of 32 keys or more).
+template <int NST, bool PAGED, bool SHARED>
 __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
                                   float lse_mul, char* ring)
 {
@@ -150,7 +151,7 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
     const int G = p.G;
     const int head = lane & 15, kg = lane >> 4;
 
-    const size_t row0 = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
+    const size_t row0 = PAGED ? 0 : ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
     const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) + row0 * kM8RowBytes;
     const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) + row0 * kM8RowBytes;
 
@@ -164,6 +165,7 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
     const int mine = wave < n_blocks ? (n_blocks - wave + kWaves - 1) / kWaves : 0;
     char* my_ring = ring + wave * (NST * kMfStageBytes);
     const uint32_t my_ring_lds = lds_address(my_ring);
+    int* my_pages = reinterpret_cast<int*>(ring + mfma_ring_bytes(NST)) + wave * kMfPageSlots;
     const float sl2 = p.scale_log2;
     constexpr int P = NST - 1;
 
@@ -177,22 +179,45 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
             qb[t] = __builtin_bit_cast(bf16x8_t, v);
         }
     }
-    const auto issue = [&](int s) {
-        const int kb = j0 + (wave + kWaves * s) * kM8BlockKeys;
-        mfma8_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kbase + (size_t)kb * kM8RowBytes,
-                          vbase + (size_t)kb * kM8RowBytes, kb, j1, lane);
-    };
-    for (int s = 0; s < P && s < mine; ++s) issue(s);
-    // the compiler's wait for the q loads goes here, outside the loop (see mfma_item)
-    asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
-    for (int s = 0; s < mine; ++s) {
-        if (s + P < mine) issue(s + P);
-        wait_stages_in_flight(min(P, mine - 1 - s));
-        if (s == 0) trace_event(p, kEvFirstStage);
-        const int kb = j0 + (wave + kWaves * s) * kM8BlockKeys;
-        const char* stage = my_ring + (s % NST) * kMfStageBytes;
-        if (kb + kM8BlockKeys <= j1) mfma8_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
-        else mfma8_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+    // chunks of blocks as in mfma_item: one for a contiguous cache, kMfPageSlots blocks at a
+    // time for a paged one, page numbers fetched into LDS while the pipeline is empty
+    const int chunk_blocks = PAGED ? kMfPageSlots : max(mine, 1);
+    for (int c0 = 0; c0 < mine; c0 += chunk_blocks) {
+        const int cmine = min(chunk_blocks, mine - c0);
+        if (PAGED) {
+            const int32_t* row = p.block_table + (size_t)b * p.pages_per_seq;
+            for (int i = lane; i < cmine; i += 64) {
+                const int kb = j0 + (wave + kWaves * (c0 + i)) * kM8BlockKeys;
+                const int pg = row[kb >> p.page_shift];
+                my_pages[i] = min(max(pg, 0), p.num_pages - 1);
+            }
+        }
+        const auto issue = [&](int s) {
+            const int kb = j0 + (wave + kWaves * (c0 + s)) * kM8BlockKeys;
+            const uint8_t *kp, *vp;
+            if (PAGED) {
+                const int pg = __builtin_amdgcn_readfirstlane(my_pages[s]);
+                const size_t first_row = (((size_t)pg * p.Hkv + kvh) << p.page_shift) + (kb & ((1 << p.page_shift) - 1));
+                kp = reinterpret_cast<const uint8_t*>(scalar_ptr(reinterpret_cast<const uint16_t*>(kbase + first_row * kM8RowBytes)));
+                vp = reinterpret_cast<const uint8_t*>(scalar_ptr(reinterpret_cast<const uint16_t*>(vbase + first_row * kM8RowBytes)));
+            } else {
+                kp = kbase + (size_t)kb * kM8RowBytes;
+                vp = vbase + (size_t)kb * kM8RowBytes;
+            }
+            mfma8_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
+        };
+        for (int s = 0; s < P && s < cmine; ++s) issue(s);
+        // the compiler's wait for the q loads goes here, outside the loop (see mfma_item)
+        asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
+        for (int s = 0; s < cmine; ++s) {
+            if (s + P < cmine) issue(s + P);
+            wait_stages_in_flight(min(P, cmine - 1 - s));
+            if (c0 + s == 0) trace_event(p, kEvFirstStage);
+            const int kb = j0 + (wave + kWaves * (c0 + s)) * kM8BlockKeys;
+            const char* stage = my_ring + (s % NST) * kMfStageBytes;
+            if (kb + kM8BlockKeys <= j1) mfma8_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
+            else mfma8_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+        }
     }
 
     trace_event(p, kEvLoopEnd);

@@ -195,6 +195,10 @@ def make_paged(inp: Inputs, page_size: int, seed: int = 0) -> PagedInputs:
     entry past a sequence's last page points at it (a read through such an entry poisons the
     result).  Rows of the last page past seq_lens[b] keep what the contiguous cache held there.
     """
+    kv_dtype = inp.k.dtype
+    k_src, v_src = inp.k, inp.v
+    if kv_dtype == torch.float8_e4m3fn:                 # moved as raw bytes; 0x7f is the E4M3 NaN
+        k_src, v_src = inp.k.view(torch.uint8), inp.v.view(torch.uint8)
     B, Hkv, S, D = inp.k.shape
     dev = inp.k.device
     max_pages = -(-S // page_size)
@@ -205,8 +209,9 @@ def make_paged(inp: Inputs, page_size: int, seed: int = 0) -> PagedInputs:
     gen.manual_seed(1000003 * page_size + seed)
     slots = torch.randperm(n_used, generator=gen).tolist()
     nan_page = n_used
-    k_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=inp.k.dtype)
-    v_pages = torch.full((n_used + 1, Hkv, page_size, D), float("nan"), device=dev, dtype=inp.k.dtype)
+    fill = 0x7F if kv_dtype == torch.float8_e4m3fn else float("nan")
+    k_pages = torch.full((n_used + 1, Hkv, page_size, D), fill, device=dev, dtype=k_src.dtype)
+    v_pages = torch.full((n_used + 1, Hkv, page_size, D), fill, device=dev, dtype=k_src.dtype)
     table = torch.full((B, max_pages), nan_page, dtype=torch.int32)
     it = iter(slots)
     for b in range(B):
@@ -214,8 +219,10 @@ def make_paged(inp: Inputs, page_size: int, seed: int = 0) -> PagedInputs:
             slot = next(it)
             table[b, pg] = slot
             lo, hi = pg * page_size, min((pg + 1) * page_size, S)
-            k_pages[slot, :, : hi - lo] = inp.k[b, :, lo:hi]
-            v_pages[slot, :, : hi - lo] = inp.v[b, :, lo:hi]
+            k_pages[slot, :, : hi - lo] = k_src[b, :, lo:hi]
+            v_pages[slot, :, : hi - lo] = v_src[b, :, lo:hi]
+    if kv_dtype == torch.float8_e4m3fn:
+        k_pages, v_pages = k_pages.view(kv_dtype), v_pages.view(kv_dtype)
     return PagedInputs(q=inp.q, k_pages=k_pages, v_pages=v_pages, block_table=table.to(dev),
                        seq_lens=inp.seq_lens, page_size=page_size)
 

@@ -716,3 +716,30 @@ def test_fp8_kv_cache_every_byte_value():
     say(f"case FP8 every byte value: |out| up to {ref_scale:.2f}")
     check_out(out.cpu().numpy(), ref_o, "fp8 all bytes")
     check_lse(lse.cpu().numpy(), ref_l, "fp8 all bytes")
+
+
+@pytest.mark.parametrize("page_size", [32, 64, 256])
+def test_fp8_kv_cache_paged(page_size):
+    wl = _generic(3, 16, 2, 2500, 1600 + page_size, ragged=True)
+    say(f"case FP8 KV cache, paged, page_size={page_size}, G=8, ragged S<=2500")
+    inp = fi.make_inputs(wl, "cuda")
+    ks, vs = 1.0 / 32, 1.0 / 16
+    inp.k, inp.v = fi.to_fp8_cache(inp, ks, vs)
+    pg = fi.make_paged(inp, page_size, seed=2)
+    ref_o, ref_l = oracle.decode_fp8kv_paged(fi.bits(pg.q), fi.bytes_of(pg.k_pages), fi.bytes_of(pg.v_pages),
+                                             pg.block_table.cpu().numpy(), pg.seq_lens.cpu().numpy(), k_scale=ks, v_scale=vs)
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=8, dtype="fp8kv", k_scale=ks, v_scale=vs) as dec:
+        for n in (1, 5, 0):
+            fd.fd_debug_poison_workspace(dec.h)
+            out_f, lse_f = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, page_size, pg.seq_lens, n)
+            out_b, lse_b = dec.decode_paged(pg.q, pg.k_pages, pg.v_pages, pg.block_table, page_size, pg.seq_lens, n, bsp=True)
+            out_c, lse_c = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, n)
+            torch.cuda.synchronize()
+            assert torch.equal(out_f.view(torch.int32), out_b.view(torch.int32)) and torch.equal(lse_f, lse_b)
+            assert torch.allclose(out_f, out_c, rtol=1e-5, atol=1e-6)
+            check_out(out_f.cpu().numpy(), ref_o, f"fp8 paged n={n}")
+            check_lse(lse_f.cpu().numpy(), ref_l, f"fp8 paged n={n}")
+        pool16 = fi.make_paged(inp, 16, seed=2)
+        with pytest.raises(fd.FdError) as e:
+            dec.decode_paged(pool16.q, pool16.k_pages, pool16.v_pages, pool16.block_table, 16, pool16.seq_lens, 1)
+        assert e.value.code == fd.FD_ERR_UNSUPPORTED

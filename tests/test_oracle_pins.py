@@ -534,3 +534,19 @@ def test_fp8kv_decode_equals_bf16_decode_on_fp8_representable_values():
     o2, l2 = oracle.decode_fp8kv(q, kb, vb, sl, k_scale=0.5, v_scale=3.0)
     o3, l3 = oracle.decode(q, k16, v16, sl, scale=0.5 / math.sqrt(D))
     assert np.allclose(o2, 3.0 * o3, rtol=1e-13, atol=1e-15) and np.allclose(l2, l3, rtol=1e-13, atol=1e-13)
+
+
+def test_fp8kv_paged_is_the_contiguous_result_wherever_pages_live():
+    rng = np.random.default_rng(41)
+    B, Hq, Hkv, D, ps = 2, 4, 2, 8, 4
+    lens = np.array([7, 10], dtype=np.int32)
+    S = 12
+    kb = rng.integers(0, 0x58, (B, Hkv, S, D)).astype(np.uint8)
+    vb = rng.integers(0, 0x78, (B, Hkv, S, D)).astype(np.uint8)
+    q = f32_to_bf16_bits(rng.standard_normal((B, Hq, D)).astype(np.float32))
+    o_ref, l_ref = oracle.decode_fp8kv(q, kb, vb, lens, k_scale=0.25, v_scale=2.0)
+    for seed in (0, 1):
+        order = np.random.default_rng(seed).permutation(B * (S // ps)).tolist()
+        kp, vp, bt = _to_pages(kb.astype(np.uint16), vb.astype(np.uint16), ps, order)
+        o, l = oracle.decode_fp8kv_paged(q, kp.astype(np.uint8), vp.astype(np.uint8), bt, lens, k_scale=0.25, v_scale=2.0)
+        assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
