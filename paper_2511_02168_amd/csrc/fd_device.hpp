@@ -155,7 +155,9 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     wlst.last = block_first(wlst.wl + 1, wlst.base, wlst.rem);
 }
 
-__device__ __forceinline__ Item worklist_item(const Params& p, const WorkList& wlst, const int* pre, int e)
+// sl_first: seq_lens[lane] of the first 64 sequences, requested when the kernel starts, so
+// that for B <= 64 the first item's length is not a load that the whole prologue waits for.
+__device__ __forceinline__ Item worklist_item(const Params& p, const WorkList& wlst, const int* pre, int e, int sl_first)
 {
     Item it;
     int k;
@@ -174,7 +176,12 @@ __device__ __forceinline__ Item worklist_item(const Params& p, const WorkList& w
     it.tile = wlst.x + p.xcd_groups * k;
     it.b = it.tile / p.Hkv;
     it.kvh = it.tile - it.b * p.Hkv;
-    it.S = seq_len_of(p, it.b);
+    if (p.B <= 64) {
+        const int s = __builtin_amdgcn_readlane(sl_first, __builtin_amdgcn_readfirstlane(it.b));
+        it.S = s < 0 ? 0 : (s > p.S_max ? p.S_max : s);
+    } else {
+        it.S = seq_len_of(p, it.b);
+    }
     it.n = num_splits_of(p, it.S);
     return it;
 }

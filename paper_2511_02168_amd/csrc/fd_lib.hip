@@ -80,13 +80,15 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
 {
     const int G = p.G;
     trace_event(p, kEvStart);
+    const int lane = threadIdx.x & 63;
+    const int sl_first = lane < p.B ? p.seq_lens[lane] : 0;     // in flight during the work-list arithmetic
     WorkList wl;
     worklist_init(p, wl, ss.pre, ss.scan_tmp);
 
     int e = wl.first;
     while (e < wl.last) {
         // a run = the splits [split, s1) of one tile that fall into this workgroup's block
-        Item it = worklist_item(p, wl, ss.pre, e);
+        Item it = worklist_item(p, wl, ss.pre, e, sl_first);
         it.tile = __builtin_amdgcn_readfirstlane(it.tile);      // all of these are workgroup-uniform
         it.b = __builtin_amdgcn_readfirstlane(it.b);
         it.kvh = __builtin_amdgcn_readfirstlane(it.kvh);
