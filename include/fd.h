@@ -191,6 +191,26 @@ int fd_decode_paged_bsp(fd_handle_t h, const void* q, const void* k_pages, const
                         void* stream);
 
 /*
+ * For callers that cannot allocate device memory or hold a handle (code recorded into a HIP
+ * graph, tight serving loops, harnesses that forbid allocation): fd_decode with the shape passed
+ * by value and the workspace in a static device array of FD_STATIC_SCRATCH_BYTES that the
+ * library's code object carries (each GPU holds it from the first use of the library until the
+ * process ends).  Arguments and results as for fd_decode on a handle made from *cfg with the
+ * default options (bitwise the same results).  The call allocates nothing on the host or the
+ * device and never synchronises; it launches one small kernel that clears the arrival counters
+ * and then the fused kernel, both on `stream`.  The first call on a device looks up the array's
+ * device address and the device's properties (make that call outside a graph capture).
+ * A shape whose workspace (fd_workspace_bytes) exceeds FD_STATIC_SCRATCH_BYTES is refused with
+ * FD_ERR_WORKSPACE: lower max_splits, or use a handle.
+ * All calls on one GPU share the one array, which keeps what the last call left: calls that
+ * overlap on one GPU (two streams, two threads) race and give undefined results; calls in
+ * stream order on one stream are safe.
+ */
+#define FD_STATIC_SCRATCH_BYTES (32u << 20)
+int fd_decode_static(const fd_config* cfg, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream);
+
+/*
  * Picks the handle's options by measurement: SYNCHRONOUS, unlike every other call here.
  * Runs fd_decode on the given arguments (3 untimed + `reps` timed calls, HIP events on
  * `stream`) for every combination of FD_OPT_XCD_GROUPS {1, 8 where allowed} with

@@ -21,7 +21,7 @@ FD_DTYPE_BF16, FD_DTYPE_FP16, FD_DTYPE_FP8_KV = 0, 1, 2
 FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH, FD_INFO_WAIT_GAVE_UP = 100, 101, 102, 103
 
 EXPORTS = ["fd_workspace_bytes", "fd_create", "fd_destroy", "fd_reset", "fd_decode", "fd_decode_bsp",
-           "fd_decode_paged", "fd_decode_paged_bsp", "fd_decode_waits", "fd_autotune", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
+           "fd_decode_paged", "fd_decode_paged_bsp", "fd_decode_waits", "fd_decode_static", "fd_autotune", "fd_set_option", "fd_get_option", "fd_debug_poison_workspace", "fd_debug_read_counters",
            "fd_debug_set_trace", "fd_debug_stream_read",
            "fd_last_error", "fd_version"]
 
@@ -63,6 +63,8 @@ def lib():
         for fn in (L.fd_decode, L.fd_decode_bsp, L.fd_decode_waits):
             fn.restype = ctypes.c_int
             fn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
+        L.fd_decode_static.restype = ctypes.c_int
+        L.fd_decode_static.argtypes = [ctypes.POINTER(fd_config), vp, vp, vp, vp, vp, vp, i32, vp]
         L.fd_set_option.restype = ctypes.c_int
         L.fd_set_option.argtypes = [vp, i32, i32]
         L.fd_get_option.restype = ctypes.c_int
@@ -150,6 +152,15 @@ def fd_decode(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream:
 def fd_decode_waits(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:
     _check(lib().fd_decode_waits(h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out), _ptr(lse),
                                  int(n_splits), ctypes.c_void_p(stream)))
+
+
+FD_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def fd_decode_static(cfg: fd_config, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:
+    """fd_decode without a handle, out of the library's static device workspace (allocates nothing)."""
+    _check(lib().fd_decode_static(ctypes.byref(cfg), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out),
+                                  _ptr(lse), int(n_splits), ctypes.c_void_p(stream)))
 
 
 def fd_decode_bsp(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits: int, stream: int = 0) -> None:

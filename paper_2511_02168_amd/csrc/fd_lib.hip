@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "fd_device.hpp"
@@ -16,11 +17,25 @@
 #include "fd_mfma.hpp"
 #include "fd_mfma8.hpp"
 
+// Workspace of fd_decode_static (the entry point for callers that cannot allocate): partials,
+// their log-sum-exps and the arrival counters of ONE call at a time, laid out as a handle's
+// workspace.  Each GPU the library runs on holds its own copy at its own address until the
+// process ends.  Host code never uses this name as an address: it asks the runtime for the
+// copy's device address once per device (static_device_state) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[FD_STATIC_SCRATCH_BYTES];
+
 namespace fd {
 
 // ---------------------------------------------------------------------------
 // Kernels
 // ---------------------------------------------------------------------------
+
+// Clears n 32-bit words (the arrival counters and the status word of the static workspace).
+// A kernel, not a memset: a caller may be recording the stream into a graph.
+__global__ __launch_bounds__(kWgThreads) void fd_zero_words_kernel(uint32_t* dst, int n)
+{
+    for (int i = blockIdx.x * kWgThreads + threadIdx.x; i < n; i += gridDim.x * kWgThreads) dst[i] = 0u;
+}
 
 // How a workgroup attends one key range: on the vector ALUs ...
 template <int G>
@@ -658,6 +673,42 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
 
 }  // namespace
 
+namespace {
+
+// Per-device set-up of fd_decode_static, done on the first call on a device (with that device
+// current): the device address of this GPU's copy of `scratch`, and the device's CU count.
+struct StaticDeviceState {
+    bool ready;
+    void* ptr;
+    int num_cus;
+};
+constexpr int kMaxStaticDevices = 64;
+StaticDeviceState g_static_dev[kMaxStaticDevices];
+std::mutex g_static_mutex;
+
+int static_device_state(int dev, StaticDeviceState* out)
+{
+    if (dev < 0 || dev >= kMaxStaticDevices) return fail(FD_ERR_UNSUPPORTED, "device index %d is out of range", dev);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticDeviceState& s = g_static_dev[dev];
+    if (!s.ready) {
+        hipDeviceProp_t prop;
+        FD_HIP(hipGetDeviceProperties(&prop, dev));
+        if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+            return fail(FD_ERR_UNSUPPORTED, "device is %s; this library is built for gfx950 only", prop.gcnArchName);
+        void* ptr = nullptr;
+        FD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) return fail(FD_ERR_HIP, "the static workspace has no usable device address");
+        s.ptr = ptr;
+        s.num_cus = prop.multiProcessorCount;
+        s.ready = true;
+    }
+    *out = s;
+    return FD_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t fd_workspace_bytes(const fd_config* cfg)
@@ -755,6 +806,42 @@ int fd_decode_waits(fd_handle_t h, const void* q, const void* k_cache, const voi
                     float* out, float* lse, int32_t n_splits, void* stream)
 {
     return decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeSignal);
+}
+
+int fd_decode_static(const fd_config* cfg, const void* q, const void* k_cache, const void* v_cache,
+                                const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream)
+{
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    const Layout lay = make_layout(*cfg);
+    if (lay.total > (size_t)FD_STATIC_SCRATCH_BYTES)
+        return fail(FD_ERR_WORKSPACE,
+                    "this shape needs %zu workspace bytes, the static workspace holds %zu: lower max_splits or use a handle",
+                    lay.total, (size_t)FD_STATIC_SCRATCH_BYTES);
+    int dev = 0;
+    FD_HIP(hipGetDevice(&dev));
+    StaticDeviceState sd;
+    rc = static_device_state(dev, &sd);
+    if (rc) return rc;
+
+    // a handle that lives on this stack frame and owns nothing
+    fd_handle_s h = {};
+    h.magic = kMagic;
+    h.cfg = *cfg;
+    h.G = cfg->Hq / cfg->Hkv;
+    h.device = dev;
+    h.num_cus = sd.num_cus;
+    h.workspace = sd.ptr;
+    h.lay = lay;
+
+    // The workspace keeps what the last call on this GPU left (possibly of another shape, possibly
+    // cut short): the counters and the status word must start at zero.
+    const int words = (int)((lay.total - lay.counters_off) / sizeof(uint32_t));
+    const int grid = words < 256 * fd::kWgThreads ? (words + fd::kWgThreads - 1) / fd::kWgThreads : 256;
+    hipLaunchKernelGGL(fd::fd_zero_words_kernel, dim3(grid), dim3(fd::kWgThreads), 0, (hipStream_t)stream,
+                       (uint32_t*)((char*)sd.ptr + lay.counters_off), words);
+    FD_HIP(hipGetLastError());
+    return decode_common(&h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
 }
 
 int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
