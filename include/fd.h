@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define FD_VERSION 130
+#define FD_VERSION 140
 
 enum {
     FD_OK = 0,
@@ -247,6 +247,7 @@ enum {
     FD_OPT_WGS_PER_CU = 3,
     FD_OPT_RING_STAGES = 4,
     FD_OPT_SPIN_LIMIT = 5,
+    FD_OPT_SPLIT_KEYS = 6,
     FD_INFO_NUM_CUS = 100,
     FD_INFO_LAST_GRID = 101,   /* workgroups of the last fused / split launch */
     FD_INFO_LAST_PATH = 102,   /* 1 VALU, 2 MFMA */

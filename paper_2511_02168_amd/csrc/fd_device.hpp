@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fd_fastdiv.hpp"
+
 namespace fd {
 
 constexpr int kD = 128;            // head dimension
@@ -20,7 +22,7 @@ constexpr int kRowU4 = kD * 2 / 16; // 16-byte chunks per K/V row (16)
 constexpr int kWgThreads = 256;
 constexpr int kWaves = kWgThreads / 64;
 constexpr int kSplitAlign = 64;    // split lengths are multiples of this many keys
-constexpr int kAdaptiveKeys = 512; // keys per split when the library chooses
+constexpr int kAdaptiveKeys = 512; // default keys per split when the library chooses
 constexpr int kMaxGroupTiles = 2048;  // tiles one XCD group can index in adaptive mode
 constexpr float kNegBig = -3.0e38f;   // finite stand-in for "no key seen yet"
 constexpr float kLn2 = 0.6931471805599453f;
@@ -45,6 +47,15 @@ struct Params {
     int32_t n_splits;         // 0 = adaptive
     int32_t max_splits;
     int32_t xcd_groups;       // 1 or 8
+    int32_t xcd_shift;        // log2(xcd_groups)
+    int32_t adaptive_keys;    // adaptive mode: keys per split the split count is derived from
+    // Fixed n_splits: what the host can work out before the launch, so that a workgroup reaches
+    // its first K/V request after a few dozen instructions.
+    int32_t split_keys;       // keys per split (from S_max, a multiple of kSplitAlign); 0 in adaptive mode
+    int32_t sched_uniform;    // 1: every XCD group has the same tiles, members and item blocks (the three below)
+    int32_t sched_members, sched_base, sched_rem;
+    FastDiv div_n_splits;     // division by n_splits (fixed mode)
+    FastDiv div_hkv;          // division by Hkv
     float scale_log2;         // softmax scale * log2(e) (FP8 cache: times k_scale)
     float out_mul;            // factor on every normalised output row: 1, or v_scale of an FP8 cache
     unsigned long long* trace;  // optional [grid][kTraceEvents] timestamps (100 MHz), or null
@@ -71,12 +82,12 @@ __device__ __forceinline__ int seq_len_of(const Params& p, int b)
 __device__ __forceinline__ int num_splits_of(const Params& p, int S)
 {
     if (p.n_splits > 0) return p.n_splits;
-    int n = (S + kAdaptiveKeys - 1) / kAdaptiveKeys;
+    int n = (S + p.adaptive_keys - 1) / p.adaptive_keys;
     n = n < 1 ? 1 : n;
     return n > p.max_splits ? p.max_splits : n;
 }
 
-__device__ __forceinline__ int split_keys_of(int S, int n)
+__host__ __device__ __forceinline__ int split_keys_of(int S, int n)
 {
     int c = (S + n - 1) / n;
     c = (c + kSplitAlign - 1) / kSplitAlign * kSplitAlign;
@@ -111,10 +122,20 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
 {
     const int X = p.xcd_groups;
     const int T = p.B * p.Hkv;
-    wlst.x = blockIdx.x % X;
-    wlst.wl = blockIdx.x / X;
-    wlst.members = (gridDim.x - wlst.x + X - 1) / X;
-    wlst.n_tiles = wlst.x < T ? (T - wlst.x + X - 1) / X : 0;
+    wlst.x = blockIdx.x & (X - 1);
+    wlst.wl = blockIdx.x >> p.xcd_shift;
+    if (p.n_splits > 0 && p.sched_uniform) {            // the usual case: nothing left to divide
+        wlst.members = p.sched_members;
+        wlst.n_tiles = T >> p.xcd_shift;
+        wlst.n_items = wlst.n_tiles * p.n_splits;
+        wlst.base = p.sched_base;
+        wlst.rem = p.sched_rem;
+        wlst.first = block_first(wlst.wl, wlst.base, wlst.rem);
+        wlst.last = block_first(wlst.wl + 1, wlst.base, wlst.rem);
+        return;
+    }
+    wlst.members = (int)(gridDim.x - wlst.x + X - 1) >> p.xcd_shift;
+    wlst.n_tiles = wlst.x < T ? (T - wlst.x + X - 1) >> p.xcd_shift : 0;
     if (p.n_splits > 0) {
         wlst.n_items = wlst.n_tiles * p.n_splits;
         wlst.base = wlst.n_items / wlst.members;
@@ -130,7 +151,7 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     int sum = 0;
     for (int k = lo; k < lo + per && k < wlst.n_tiles; ++k) {
         const int t = wlst.x + X * k;
-        sum += num_splits_of(p, seq_len_of(p, t / p.Hkv));
+        sum += num_splits_of(p, seq_len_of(p, (int)fast_div((uint32_t)t, p.div_hkv)));
     }
     scan_tmp[tid] = sum;
     __syncthreads();
@@ -144,7 +165,7 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     for (int k = lo; k < lo + per && k < wlst.n_tiles; ++k) {
         pre[k] = run;
         const int t = wlst.x + X * k;
-        run += num_splits_of(p, seq_len_of(p, t / p.Hkv));
+        run += num_splits_of(p, seq_len_of(p, (int)fast_div((uint32_t)t, p.div_hkv)));
     }
     if (tid == kWgThreads - 1) pre[wlst.n_tiles] = scan_tmp[tid];
     __syncthreads();
@@ -155,27 +176,36 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
     wlst.last = block_first(wlst.wl + 1, wlst.base, wlst.rem);
 }
 
+// Which tile and split item e of a fixed-n_splits work list is: needs no sequence length, so a
+// workgroup can aim its first K/V request before seq_lens has arrived.
+__device__ __forceinline__ void fixed_item_place(const Params& p, const WorkList& wlst, int e, Item& it)
+{
+    const int k = (int)fast_div((uint32_t)e, p.div_n_splits);
+    it.split = e - k * p.n_splits;
+    it.tile = wlst.x + (k << p.xcd_shift);
+    it.b = (int)fast_div((uint32_t)it.tile, p.div_hkv);
+    it.kvh = it.tile - it.b * p.Hkv;
+    it.n = p.n_splits;
+}
+
 // sl_first: seq_lens[lane] of the first 64 sequences, requested when the kernel starts, so
 // that for B <= 64 the first item's length is not a load that the whole prologue waits for.
 __device__ __forceinline__ Item worklist_item(const Params& p, const WorkList& wlst, const int* pre, int e, int sl_first)
 {
     Item it;
-    int k;
     if (p.n_splits > 0) {
-        k = e / p.n_splits;
-        it.split = e - k * p.n_splits;
+        fixed_item_place(p, wlst, e, it);
     } else {
         int lo = 0, hi = wlst.n_tiles;      // largest k with pre[k] <= e
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (pre[mid] <= e) lo = mid; else hi = mid;
         }
-        k = lo;
-        it.split = e - pre[k];
+        it.split = e - pre[lo];
+        it.tile = wlst.x + (lo << p.xcd_shift);
+        it.b = (int)fast_div((uint32_t)it.tile, p.div_hkv);
+        it.kvh = it.tile - it.b * p.Hkv;
     }
-    it.tile = wlst.x + p.xcd_groups * k;
-    it.b = it.tile / p.Hkv;
-    it.kvh = it.tile - it.b * p.Hkv;
     if (p.B <= 64) {
         const int s = __builtin_amdgcn_readlane(sl_first, __builtin_amdgcn_readfirstlane(it.b));
         it.S = s < 0 ? 0 : (s > p.S_max ? p.S_max : s);
@@ -237,6 +267,8 @@ __device__ __forceinline__ float load_agent(const float* p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// the same wait, where it stands for "every K/V transfer this wave requested has landed in LDS"
+__device__ __forceinline__ void wait_loads_landed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x)
@@ -364,7 +396,7 @@ __device__ inline void combine_tile_unstaged(const float* plse, const float* po,
     }
 }
 
-// Combine of one tile (Algorithm 4 Part 2; Equations of Section 4.2.1) by the workgroup
+// Combine of one tile (Algorithm 4 Part 2: the log-sum-exp merge of the partials) by the workgroup
 // that saw the last arrival.  BATCH = rows whose loads a thread keeps in flight (a
 // multiple of kCombineGroup).
 //
@@ -394,9 +426,57 @@ struct TileSchedule {
     int t0, base, rem, members, split_keys, S;
 };
 
+// Row slices of a combine: R = 2^log_r threads share one (head, 4 dims) pair, R the largest
+// power of two with R * G * 32 <= 256.
+__device__ __forceinline__ int combine_log_r(int G) { return G >= 5 ? 0 : G >= 3 ? 1 : G == 2 ? 2 : 3; }
+__device__ __forceinline__ int combine_live_stride(int log_r) { return (kMaxSplits >> log_r) + 32; }
+
+// Pads the live list to whole row groups (the padding re-reads the first live row with weight 0)
+// and publishes the count.  Wave 0 only.
+__device__ __forceinline__ void combine_live_finish(CombineSmem& sm, int count, int live0, int log_r, int lane)
+{
+    const int R = 1 << log_r, stride = combine_live_stride(log_r);
+    for (int k = count + lane; k < count + R * (kCombineGroup + 1); k += 64)
+        sm.live[(k & (R - 1)) * stride + (k >> log_r)] = live0;
+    if (lane == 0) sm.n_live = count;
+}
+
+// The live slots of a tile of the fused kernel follow from the schedule: no memory access.
+// Wave 0 only (all 64 lanes).  It does not depend on anything another workgroup does, so the
+// fused kernel runs it while its arrival count is still on its way back from memory.
+__device__ inline void combine_live_from_schedule(CombineSmem& sm, const TileSchedule& sch, int n, int G)
+{
+    const int lane = threadIdx.x & 63;
+    const int log_r = combine_log_r(G), R = 1 << log_r, stride = combine_live_stride(log_r);
+    int count = 0, live0 = 0;
+    // Candidate blocks: a range that surely contains every block holding an item of [t0, t0 + n)
+    // (block w starts at or after w * base and before (w + 1) * (base + 1))
+    const int t0 = sch.t0, members = sch.members;
+    int w_first = 0, w_end = members;
+    if (sch.base > 0) {
+        w_first = max(0, (int)((float)t0 * __builtin_amdgcn_rcpf((float)(sch.base + 1))) - 1);
+        w_end = min(members, (int)((float)(t0 + n) * __builtin_amdgcn_rcpf((float)sch.base)) + 2);
+    }
+#pragma nounroll
+    for (int w0 = w_first; w0 < w_end; w0 += 64) {
+        const int w = w0 + lane;
+        const int lo = max(block_first(w, sch.base, sch.rem), t0);
+        const int hi = min(block_first(w + 1, sch.base, sch.rem), t0 + n);
+        const bool live = w < w_end && lo < hi && (long long)(lo - t0) * sch.split_keys < sch.S;
+        const unsigned long long mask = __ballot(live);
+        const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
+        if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = lo - t0;
+        if (count == 0 && mask != 0) live0 = __builtin_amdgcn_readlane(lo - t0, __builtin_ctzll(mask));
+        count += __popcll(mask);
+    }
+    combine_live_finish(sm, count, live0, log_r, lane);
+}
+
+// live_ready: the live list is already in sm (combine_live_from_schedule); otherwise wave 0
+// finds the live slots by reading head 0's lse of every slot.
 template <int BATCH>
 __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm,
-                                    const TileSchedule* sch = nullptr)
+                                    bool live_ready = false)
 {
     static_assert(BATCH % kCombineGroup == 0 && BATCH <= 32, "row batch");
     const int G = p.G;          // <= 16
@@ -411,64 +491,35 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     float* out_rows = p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD;
     float* lse_rows = p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr;
 
-    // R = row slices = largest power of two with R * (pairs) <= 256
     const int kPairs = G * (kD / 4);
-    const int log_r = G >= 5 ? 0 : G >= 3 ? 1 : G == 2 ? 2 : 3;
+    const int log_r = combine_log_r(G);
     const int R = 1 << log_r;
-    const int stride = (kMaxSplits >> log_r) + 32;       // of one slice's live list
+    const int stride = combine_live_stride(log_r);       // of one slice's live list
 
-    if (tid < 64) {
+    if (tid < 64 && !live_ready) {
         int count = 0, live0 = 0;
-        if (sch) {
-            // the live slots follow from the schedule: no memory access.  Candidate blocks:
-            // a range that surely contains every block holding an item of [t0, t0 + n)
-            // (block w starts at or after w * base and before (w + 1) * (base + 1))
-            const int t0 = sch->t0, members = sch->members;
-            int w_first = 0, w_end = members;
-            if (sch->base > 0) {
-                w_first = max(0, (int)((float)t0 * __builtin_amdgcn_rcpf((float)(sch->base + 1))) - 1);
-                w_end = min(members, (int)((float)(t0 + n) * __builtin_amdgcn_rcpf((float)sch->base)) + 2);
-            }
 #pragma nounroll
-            for (int w0 = w_first; w0 < w_end; w0 += 64) {
-                const int w = w0 + lane;
-                const int lo = max(block_first(w, sch->base, sch->rem), t0);
-                const int hi = min(block_first(w + 1, sch->base, sch->rem), t0 + n);
-                const bool live = w < w_end && lo < hi && (long long)(lo - t0) * sch->split_keys < sch->S;
-                const unsigned long long mask = __ballot(live);
-                const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
-                if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = lo - t0;
-                if (count == 0 && mask != 0)
-                    live0 = __builtin_amdgcn_readlane(lo - t0, __builtin_ctzll(mask));
-                count += __popcll(mask);
+        for (int base = 0; base < n; base += 256) {      // one trip up to 256 slots
+            float first[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = base + j * 64 + lane;
+                first[j] = -INFINITY;
+                if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * G]);
             }
-        } else {
-#pragma nounroll
-            for (int base = 0; base < n; base += 256) {      // one trip up to 256 slots
-                float first[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = base + j * 64 + lane;
-                    first[j] = -INFINITY;
-                    if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * G]);
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (base + j * 64 < n) {
-                        const bool live = first[j] != -INFINITY;
-                        const unsigned long long mask = __ballot(live);
-                        const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
-                        if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
-                        if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
-                        count += __popcll(mask);
-                    }
+            for (int j = 0; j < 4; ++j) {
+                if (base + j * 64 < n) {
+                    const bool live = first[j] != -INFINITY;
+                    const unsigned long long mask = __ballot(live);
+                    const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
+                    if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
+                    if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
+                    count += __popcll(mask);
                 }
             }
         }
-        // padding up to the next multiple of R * kCombineGroup rows re-reads the first live row
-        for (int k = count + lane; k < count + R * (kCombineGroup + 1); k += 64)
-            sm.live[(k & (R - 1)) * stride + (k >> log_r)] = live0;
-        if (lane == 0) sm.n_live = count;
+        combine_live_finish(sm, count, live0, log_r, lane);
     }
     trace_event(p, kEvCombA);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");

@@ -40,35 +40,48 @@ __global__ __launch_bounds__(kWgThreads) void fd_zero_words_kernel(uint32_t* dst
 // How a workgroup attends one key range: on the vector ALUs ...
 template <int G>
 struct ValuPath {
+    static constexpr bool kPrefetch = false;
     ItemSmem<G>* sm;
+    __device__ __forceinline__ void prefetch(const Params&, int, int, int, int, MfmaPrefetch&) const {}
     template <bool SHARED>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
-                                         float mul) const
+                                         float mul, MfmaPrefetch&) const
     {
         valu_item<G, SHARED>(p, b, kvh, j0, j1, o, l, mul, *sm);
     }
 };
 
-// ... or on the matrix cores, through an LDS ring of NST stages per wave.
+// ... or on the matrix cores, through an LDS ring of NST stages per wave.  With a contiguous
+// cache the first key range's first stages can be requested before the range's end is known.
 template <int NST, bool PAGED, bool F16>
 struct MfmaPath {
+    static constexpr bool kPrefetch = !PAGED;
     char* ring;
+    __device__ __forceinline__ void prefetch(const Params& p, int b, int kvh, int j0, int j1_max, MfmaPrefetch& pf) const
+    {
+        mfma_prefetch<NST>(p, b, kvh, j0, j1_max, ring, pf);
+    }
     template <bool SHARED>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
-                                         float mul) const
+                                         float mul, MfmaPrefetch& pf) const
     {
-        mfma_item<NST, PAGED, F16, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+        mfma_item<NST, PAGED, F16, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring, pf);
     }
 };
 
 template <int NST, bool PAGED>
 struct Mfma8Path {
+    static constexpr bool kPrefetch = !PAGED;
     char* ring;
+    __device__ __forceinline__ void prefetch(const Params& p, int b, int kvh, int j0, int j1_max, MfmaPrefetch& pf) const
+    {
+        mfma8_prefetch<NST>(p, b, kvh, j0, j1_max, ring, pf);
+    }
     template <bool SHARED>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
-                                         float mul) const
+                                         float mul, MfmaPrefetch& pf) const
     {
-        mfma8_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring);
+        mfma8_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring, pf);
     }
 };
 
@@ -101,6 +114,21 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
     worklist_init(p, wl, ss.pre, ss.scan_tmp);
 
     int e = wl.first;
+    // Fixed n_splits: where the first key range starts does not depend on the sequence length
+    // (splits are cut from S_max), so q and the first stage of every wave are requested now,
+    // while seq_lens is still on its way; the range's end is settled when it arrives.
+    MfmaPrefetch pf;
+    pf.reset();
+    if (Path::kPrefetch && p.n_splits > 0 && e < wl.last) {
+        Item it0;
+        fixed_item_place(p, wl, e, it0);
+        const int s1 = min(p.n_splits, it0.split + (wl.last - e));
+        const int j0 = it0.split * p.split_keys;
+        const int j1_max = min(s1 * p.split_keys, p.S_max);
+        if (j0 < j1_max)
+            path.prefetch(p, __builtin_amdgcn_readfirstlane(it0.b), __builtin_amdgcn_readfirstlane(it0.kvh), j0, j1_max, pf);
+    }
+
     while (e < wl.last) {
         // a run = the splits [split, s1) of one tile that fall into this workgroup's block
         Item it = worklist_item(p, wl, ss.pre, e, sl_first);
@@ -114,17 +142,23 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
         const int run = s1 - it.split;
         const int t0 = e - it.split;         // the tile's first item in this work list
         e += run;
-        const int c = split_keys_of(it.S, it.n);
+        // keys per split: from S_max for a fixed split count (known before the launch), from the
+        // sequence's own length when the library chose the count
+        const int c = p.n_splits > 0 ? p.split_keys : split_keys_of(it.S, it.n);
         const int j0 = min(it.split * c, it.S);
         const int j1 = min(s1 * c, it.S);
         const size_t slot = (size_t)it.tile * p.max_splits + it.split;
         const bool direct = run == it.n;     // the whole tile in one go: this is the final result
+        if (Path::kPrefetch && pf.any() && j0 >= j1) {           // the prefetched range turned out empty
+            wait_loads_landed();
+            pf.reset();
+        }
 
         if (direct) {
             float* o = p.out + ((size_t)it.b * p.Hq + (size_t)it.kvh * G) * kD;
             float* l = p.lse ? p.lse + (size_t)it.b * p.Hq + it.kvh * G : nullptr;
             if (j0 < j1) {
-                path.template item<false>(p, it.b, it.kvh, j0, j1, o, l, kLn2);
+                path.template item<false>(p, it.b, it.kvh, j0, j1, o, l, kLn2, pf);
             } else {                         // empty sequence: out = 0, lse = -inf
                 for (int i = threadIdx.x; i < G * kD; i += kWgThreads) o[i] = 0.f;
                 if (l && threadIdx.x < G) l[threadIdx.x] = -INFINITY;
@@ -143,7 +177,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
         // a6: one partial for the run in its first slot; the run's other slots (and
         // the first one too if the run has no keys) are marked empty
         if (j0 < j1)
-            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f);
+            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f, pf);
         {
             const int skip = j0 < j1 ? G : 0;
             for (int i = skip + threadIdx.x; i < run * G; i += kWgThreads)
@@ -155,20 +189,24 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             // a7: the partial went out with coherent stores; once they are acknowledged
             // and every wave has reached the barrier, one thread counts the run's splits
             // as arrived (Algorithm 4: push, then atomic increment of the flag).
-            // a8: whoever completes the tile's count combines it.
+            // a8: whoever completes the tile's count combines it.  While the count is on its
+            // way back, wave 0 already lists the tile's live slots from the schedule (wasted
+            // on every workgroup but the last, which have nothing else to do then).
             wait_stores_done();
             trace_event(p, kEvStoresAcked);
             __syncthreads();
-            if (threadIdx.x == 0) {
-                const uint32_t old = __hip_atomic_fetch_add(&p.counters[it.tile], (uint32_t)run, __ATOMIC_RELAXED,
-                                                            __HIP_MEMORY_SCOPE_AGENT);
-                ss.is_last = old + (uint32_t)run == (uint32_t)it.n;
+            uint32_t old = 0;
+            if (threadIdx.x == 0)
+                old = __hip_atomic_fetch_add(&p.counters[it.tile], (uint32_t)run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (MODE == kModeFused && threadIdx.x < 64) {
+                const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
+                combine_live_from_schedule(comb, sch, it.n, G);
             }
+            if (threadIdx.x == 0) ss.is_last = old + (uint32_t)run == (uint32_t)it.n;
             __syncthreads();
             trace_event(p, kEvCounted);
             if (MODE == kModeFused && ss.is_last) {
-                const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
-                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, &sch);
+                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, true);
                 if (threadIdx.x == 0)                               // re-arm for the next call
                     __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 trace_event(p, kEvCombined);
@@ -209,11 +247,11 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_kernel(Params p)
 }
 
 // The MFMA kernel over an FP8 (E4M3) KV cache: 32-key stages converted to bf16 between LDS and the matrix cores.
-template <bool FUSED, int CB, bool PAGED>
+template <int NST, bool FUSED, int CB, bool PAGED>
 __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma8_kernel(Params p)
 {
     __shared__ SchedSmem ss;
-    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, Mfma8Path<2, PAGED>{fd_dyn_smem}, ss,
+    persistent_loop<(FUSED ? kModeFused : kModeBsp), CB>(p, Mfma8Path<NST, PAGED>{fd_dyn_smem}, ss,
                                                         *reinterpret_cast<CombineSmem*>(fd_dyn_smem));
 }
 
@@ -353,7 +391,7 @@ struct fd_handle_s {
     int num_cus;
     void* workspace;
     Layout lay;
-    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring, opt_spin_limit;
+    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring, opt_spin_limit, opt_split_keys;
     hipStream_t side_stream;      // fine-grained waits: the waiting combine kernel runs here
     hipEvent_t ev_fork, ev_join;
     int last_grid, last_path;
@@ -463,26 +501,26 @@ int launch_mfma(const fd::Params& p, bool fused, int grid, hipStream_t st)
     return launch_combine(p, st);
 }
 
-template <int CB, bool PAGED>
+template <int NST, int CB, bool PAGED>
 int launch_mfma8(const fd::Params& p, bool fused, int grid, hipStream_t st)
 {
     static thread_local int granted_device[2] = {-1, -1};
     int dev = 0;
     FD_HIP(hipGetDevice(&dev));
-    const size_t lds = (size_t)fd::mfma_lds_bytes(2);
+    const size_t lds = (size_t)fd::mfma_lds_bytes(NST);
     if (granted_device[fused] != dev) {
         if (fused)
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<true, CB, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<NST, true, CB, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         else
-            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<false, CB, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            FD_HIP(hipFuncSetAttribute((const void*)fd::fd_mfma8_kernel<NST, false, CB, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         granted_device[fused] = dev;
     }
     if (fused) {
-        hipLaunchKernelGGL((fd::fd_mfma8_kernel<true, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+        hipLaunchKernelGGL((fd::fd_mfma8_kernel<NST, true, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
         FD_HIP(hipGetLastError());
         return FD_OK;
     }
-    hipLaunchKernelGGL((fd::fd_mfma8_kernel<false, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
+    hipLaunchKernelGGL((fd::fd_mfma8_kernel<NST, false, CB, PAGED>), dim3(grid), dim3(fd::kWgThreads), lds, st, p);
     FD_HIP(hipGetLastError());
     return launch_combine(p, st);
 }
@@ -584,7 +622,8 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     const long long items_max = (long long)tiles * (n_splits > 0 ? n_splits : c.max_splits);
     int per_cu = h->opt_wgs_per_cu > 0 ? h->opt_wgs_per_cu : ((path == 2 || G >= 4) ? 1 : 2);
     if (mode == fd::kModeSignal) per_cu = 1;
-    if (path == 2 && per_cu > 2) per_cu = 2;
+    if (path == 2 && per_cu > 2)
+        return fail(FD_ERR_INVALID_ARG, "the MFMA kernel runs 1 or 2 workgroups per CU (FD_OPT_WGS_PER_CU = %d)", per_cu);
     long long grid = (long long)h->num_cus * per_cu;
     if (grid > items_max) grid = items_max;
     int X = h->opt_xcd;
@@ -620,6 +659,19 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.n_splits = n_splits;
     p.max_splits = c.max_splits;
     p.xcd_groups = X;
+    p.xcd_shift = X == 8 ? 3 : 0;
+    p.adaptive_keys = h->opt_split_keys > 0 ? h->opt_split_keys : fd::kAdaptiveKeys;
+    p.split_keys = n_splits > 0 ? fd::split_keys_of(c.S_max, n_splits) : 0;
+    p.div_n_splits = fd::make_fastdiv((uint32_t)(n_splits > 0 ? n_splits : 1));
+    p.div_hkv = fd::make_fastdiv((uint32_t)c.Hkv);
+    p.sched_uniform = n_splits > 0 && tiles % X == 0 && grid % X == 0;
+    p.sched_members = p.sched_base = p.sched_rem = 0;
+    if (p.sched_uniform) {
+        const long long members = grid / X, n_items = (long long)(tiles / X) * n_splits;
+        p.sched_members = (int32_t)members;
+        p.sched_base = (int32_t)(n_items / members);
+        p.sched_rem = (int32_t)(n_items % members);
+    }
     const float scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.D);
     p.scale_log2 = scale * 1.4426950408889634f;
     p.out_mul = 1.0f;
@@ -640,8 +692,11 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         if (h->cfg.dtype == FD_DTYPE_FP8_KV)
         {
             if (pg.table)
-                return two ? launch_mfma8<8, true>(p, fused, (int)grid, st) : launch_mfma8<32, true>(p, fused, (int)grid, st);
-            return two ? launch_mfma8<8, false>(p, fused, (int)grid, st) : launch_mfma8<32, false>(p, fused, (int)grid, st);
+                return two ? launch_mfma8<2, 8, true>(p, fused, (int)grid, st) : launch_mfma8<2, 32, true>(p, fused, (int)grid, st);
+            if (two) return launch_mfma8<2, 8, false>(p, fused, (int)grid, st);
+            if (nst == 4) return launch_mfma8<4, 32, false>(p, fused, (int)grid, st);
+            if (nst == 3) return launch_mfma8<3, 32, false>(p, fused, (int)grid, st);
+            return launch_mfma8<2, 32, false>(p, fused, (int)grid, st);
         }
         if (h->cfg.dtype == FD_DTYPE_FP16) {           // the half and the paged kernels are built for the default ring depth
             if (pg.table)
@@ -737,7 +792,7 @@ int fd_create(const fd_config* cfg, fd_handle_t* out)
     h->device = dev;
     h->num_cus = prop.multiProcessorCount;
     h->lay = make_layout(*cfg);
-    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = h->opt_spin_limit = 0;
+    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = h->opt_spin_limit = h->opt_split_keys = 0;
     h->side_stream = nullptr;
     h->ev_fork = h->ev_join = nullptr;
     h->last_grid = h->last_path = 0;
@@ -762,6 +817,7 @@ int fd_create(const fd_config* cfg, fd_handle_t* out)
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(h->workspace);
+        release_sync_objects(h);
         delete h;
         return fail(FD_ERR_HIP, "zeroing the counters failed: %s", hipGetErrorString(e));
     }
@@ -858,26 +914,41 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
         return fail(FD_ERR_HIP, "hipEventCreate failed");
     }
     const int tiles = h->cfg.B * h->cfg.Hkv;
-    // candidates: {work lists} x {(workgroups per CU, ring stages)}, MFMA kernel; plus the VALU kernel where it is built
-    struct Cand { int path, xcd, per_cu, ring; };
-    Cand cands[16];
+    const bool bf16 = h->cfg.dtype == FD_DTYPE_BF16;
+    // The joint search space (the one-GPU counterpart of tuning the transfer granularity together
+    // with the kernel's tiling, paper Section 6.3): how finely a tile is cut when the library picks
+    // the split count x the work-list shape x (workgroups per CU, ring stages) of the MFMA kernel,
+    // plus the VALU kernel; only what this handle's dtype is built for.
+    struct Cand { int path, xcd, per_cu, ring, split_keys; };
+    Cand cands[96];
     int n_cand = 0;
     const int xcds[2] = {1, 8};
-    const int shapes[4][2] = {{1, 2}, {1, 3}, {1, 4}, {2, 2}};
-    for (int xi = 0; xi < 2; ++xi) {
-        if (xcds[xi] == 8 && tiles % 8 != 0) continue;
-        for (int si = 0; si < 4; ++si) cands[n_cand++] = Cand{2, xcds[xi], shapes[si][0], shapes[si][1]};
-        if (h->G <= 8) cands[n_cand++] = Cand{1, xcds[xi], 0, 0};
+    const int shapes[4][2] = {{1, 2}, {2, 2}, {1, 3}, {1, 4}};
+    const int n_shapes = bf16 ? 4 : 2;                        // deeper rings are built for bf16 only
+    const int grains[4] = {512, 256, 1024, 2048};
+    const int n_grains = n_splits == 0 ? 4 : 1;               // a fixed split count is the caller's choice
+    for (int gi = 0; gi < n_grains; ++gi) {
+        const int grain = n_splits == 0 ? grains[gi] : 0;
+        for (int xi = 0; xi < 2; ++xi) {
+            if (xcds[xi] == 8 && tiles % 8 != 0) continue;
+            for (int si = 0; si < n_shapes; ++si) cands[n_cand++] = Cand{2, xcds[xi], shapes[si][0], shapes[si][1], grain};
+            if (bf16 && h->G <= 8) cands[n_cand++] = Cand{1, xcds[xi], 0, 0, grain};
+        }
     }
-    const Cand saved = {h->opt_path, h->opt_xcd, h->opt_wgs_per_cu, h->opt_ring};
+    const Cand saved = {h->opt_path, h->opt_xcd, h->opt_wgs_per_cu, h->opt_ring, h->opt_split_keys};
+    const auto apply = [&](const Cand& c) {
+        h->opt_path = c.path; h->opt_xcd = c.xcd; h->opt_wgs_per_cu = c.per_cu; h->opt_ring = c.ring; h->opt_split_keys = c.split_keys;
+    };
     float best = 0.f;
     int best_i = -1;
     rc = FD_OK;
     for (int i = 0; i < n_cand && rc == FD_OK; ++i) {
-        h->opt_path = cands[i].path; h->opt_xcd = cands[i].xcd; h->opt_wgs_per_cu = cands[i].per_cu; h->opt_ring = cands[i].ring;
-        for (int w = 0; w < 3 && rc == FD_OK; ++w)
-            rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
-        if (rc != FD_OK) break;
+        apply(cands[i]);
+        int r1 = FD_OK;
+        for (int w = 0; w < 3 && r1 == FD_OK; ++w)
+            r1 = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
+        if (r1 == FD_ERR_UNSUPPORTED) continue;                // a combination this shape does not allow: not a failure
+        if (r1 != FD_OK) { rc = r1; break; }
         if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(FD_ERR_HIP, "hipEventRecord failed"); break; }
         for (int r = 0; r < reps && rc == FD_OK; ++r)
             rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
@@ -894,11 +965,17 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc != FD_OK || best_i < 0) {
-        h->opt_path = saved.path; h->opt_xcd = saved.xcd; h->opt_wgs_per_cu = saved.per_cu; h->opt_ring = saved.ring;
-        return rc != FD_OK ? rc : fail(FD_ERR_HIP, "no candidate could be timed");
+        apply(saved);
+        return rc != FD_OK ? rc : fail(FD_ERR_UNSUPPORTED, "no option combination is built for this shape");
     }
-    h->opt_path = cands[best_i].path; h->opt_xcd = cands[best_i].xcd; h->opt_wgs_per_cu = cands[best_i].per_cu;
-    h->opt_ring = cands[best_i].ring;
+    apply(cands[best_i]);
+    // leave out / lse holding a result of the chosen combination
+    rc = decode_common(h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
+    if (rc == FD_OK && hipStreamSynchronize(st) != hipSuccess) rc = fail(FD_ERR_HIP, "hipStreamSynchronize failed");
+    if (rc != FD_OK) {
+        apply(saved);
+        return rc;
+    }
     if (best_us) *best_us = best;
     return FD_OK;
 }
@@ -946,6 +1023,11 @@ int fd_set_option(fd_handle_t h, int32_t key, int32_t value)
             if (value != 0 && (value < 2 || value > 4)) return fail(FD_ERR_INVALID_ARG, "FD_OPT_RING_STAGES must be 0, 2, 3 or 4");
             h->opt_ring = value;
             return FD_OK;
+        case FD_OPT_SPLIT_KEYS:
+            if (value != 0 && (value < fd::kSplitAlign || value > 65536 || value % fd::kSplitAlign))
+                return fail(FD_ERR_INVALID_ARG, "FD_OPT_SPLIT_KEYS must be 0 or a multiple of %d in %d..65536", fd::kSplitAlign, fd::kSplitAlign);
+            h->opt_split_keys = value;
+            return FD_OK;
         default:
             return fail(FD_ERR_INVALID_ARG, "unknown or read-only option %d", key);
     }
@@ -962,6 +1044,7 @@ int fd_get_option(fd_handle_t h, int32_t key, int32_t* value)
         case FD_OPT_WGS_PER_CU: *value = h->opt_wgs_per_cu; return FD_OK;
         case FD_OPT_RING_STAGES: *value = h->opt_ring; return FD_OK;
         case FD_OPT_SPIN_LIMIT: *value = h->opt_spin_limit; return FD_OK;
+        case FD_OPT_SPLIT_KEYS: *value = h->opt_split_keys; return FD_OK;
         case FD_INFO_WAIT_GAVE_UP: {
             uint32_t flag = 0;
             FD_HIP(hipDeviceSynchronize());

@@ -1,5 +1,6 @@
-// Partial attention of one key range on the matrix cores (GQA group >= 8: the
-// group's query rows fill at least half of a 16-row MFMA tile).
+// Partial attention of one key range on the matrix cores: the default kernel for every
+// GQA group size up to 16 (the group's query rows are the columns of a 16-wide MFMA tile;
+// below 16 the rest is padding, which the HBM bound hides).
 //
 // Steps a2-a6 of the hot path (paper Section 4.2.1, Algorithm 4 Part 1) for up
 // to 16 query heads that share one KV head.
@@ -94,8 +95,13 @@ __device__ __forceinline__ uint32_t lds_address(const void* p)
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
+// How far (base-2 units) a score may exceed the running reference maximum before the
+// accumulators are rescaled.
+constexpr float kRescaleSlack = 6.0f;
+
 struct MfmaState {
-    float m;            // running max of head (lane & 15), base-2 units, same in the 4 lanes of a head
+    float m;            // reference maximum of head (lane & 15), base-2 units, same in the 4 lanes of a head:
+                        // at least (largest score seen) - kRescaleSlack
     float l;            // this lane's share of the running sum (its 4 keys per block)
     f32x4_t acc[8];     // O^T: block db, element e = dim 16*db + 4*(lane>>4) + e of head (lane & 15)
 };
@@ -161,8 +167,12 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
     float tm = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3]));
     tm = fmaxf(tm, __shfl_xor(tm, 16));
     tm = fmaxf(tm, __shfl_xor(tm, 32));
-    const float mnew = fmaxf(st.m, tm);
-    if (__any(mnew > st.m)) {
+    // The reference maximum st.m only moves when some head's scores exceed it by more than
+    // kRescaleSlack (then every head moves to its current maximum): weights stay below
+    // 2^kRescaleSlack, which fp32 sums and the hi + lo split below carry without loss, and the
+    // rescale of the accumulators becomes a rare event instead of one per new maximum.
+    if (__any(tm > st.m + kRescaleSlack)) {
+        const float mnew = fmaxf(st.m, tm);
         const float alpha = fast_exp2(st.m - mnew);
         st.m = mnew;
         st.l *= alpha;
@@ -180,9 +190,10 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
             phi[e] = __builtin_bit_cast(short, hi);
             plo[e] = __builtin_bit_cast(short, lo);
         } else {
-            const __bf16 hi = (__bf16)p[e];
-            const __bf16 lo = (__bf16)(p[e] - (float)hi);
-            phi[e] = __builtin_bit_cast(short, hi);
+            // hi = p cut to its upper 16 bits (a bf16 value), lo = the exact rest, rounded to bf16
+            const uint32_t bits = __builtin_bit_cast(uint32_t, p[e]);
+            const __bf16 lo = (__bf16)(p[e] - __builtin_bit_cast(float, bits & 0xffff0000u));
+            phi[e] = (short)(bits >> 16);
             plo[e] = __builtin_bit_cast(short, lo);
         }
     }
@@ -209,6 +220,49 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
     }
 }
 
+// What a workgroup requested for its first key range before the range's end was known (the
+// sequence length still on its way): the query group, and stage 0 of every wave, aimed at the
+// split's nominal start.  Consumed by the first mfma_item call, which checks it against the range.
+struct MfmaPrefetch {
+    bf16x8_t qb[4];
+    int j0;          // start of the range the stages were aimed at; -1 = nothing requested
+    __device__ __forceinline__ void reset() { j0 = -1; }
+    __device__ __forceinline__ bool any() const { return j0 >= 0; }
+};
+
+// a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero.
+__device__ __forceinline__ void mfma_load_q(const Params& p, int b, int kvh, int lane, bf16x8_t (&qb)[4])
+{
+    const int head = lane & 15, kg = lane >> 4;
+    const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * p.G + head) * kRowU4;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (head < p.G) v = qp[4 * t + kg];
+        qb[t] = __builtin_bit_cast(bf16x8_t, v);
+    }
+}
+
+// Requests q and each wave's first 16-key block of the range starting at j0 of tile (b, kvh),
+// knowing only that the range ends at or before j1_max <= S_max (contiguous cache).  Rows up to
+// j1_max - 1 may be read: inside the cache, possibly past the sequence's end; a block that turns
+// out not to lie wholly inside the real range is requested again by mfma_item, so what was read
+// past the end is never used.
+template <int NST>
+__device__ __forceinline__ void mfma_prefetch(const Params& p, int b, int kvh, int j0, int j1_max, char* ring,
+                                              MfmaPrefetch& pf)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    mfma_load_q(p, b, kvh, lane, pf.qb);
+    pf.j0 = j0;
+    const int kb = j0 + wave * kMfBlockKeys;
+    if (kb < j1_max) {
+        const size_t row = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max + (size_t)kb;
+        mfma_issue_stage(lds_address(ring + wave * (NST * kMfStageBytes)), p.k + row * kD, p.v + row * kD, kb, j1_max, lane);
+    }
+}
+
 // Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) for its G <= 16 query heads.
 // ring: this workgroup's LDS ring (mfma_ring_bytes(NST) bytes, 16-byte aligned);
 // it doubles as the ItemSmem<16> staging at the end of the range.
@@ -216,7 +270,7 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
 // dst_lse[G] (SHARED as in item_finish).  Leaves LDS free for reuse on return.
 template <int NST, bool PAGED, bool F16, bool SHARED>
 __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
-                                 float lse_mul, char* ring)
+                                 float lse_mul, char* ring, MfmaPrefetch& pf)
 {
     static_assert(NST >= 2 && NST <= 8, "ring depth");
     static_assert(sizeof(ItemSmem<kMfRows>) <= (size_t)mfma_ring_bytes(2), "staging must fit the ring");
@@ -247,17 +301,20 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     const float sl2 = p.scale_log2;
     constexpr int P = NST - 1;                            // stages in flight ahead of the one being consumed
 
-    // a2: B operand of QK^T: lane (head, kg) holds dims 8*(4t + kg) .. +7 of its head; rows >= G are zero.
-    // Requested first: the round trip overlaps the issue of the first stages.
+    // a2: the query group, requested first (the round trip overlaps the issue of the first stages),
+    // unless the prefetch already did.  This wave's stage 0 counts as requested if the prefetch
+    // aimed at this range and the block lies wholly inside it; a prefetched block that does not
+    // is waited for and requested again below.
     bf16x8_t qb[4];
-    {
-        const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * G + head) * kRowU4;
+    bool stage0_requested = false;
+    if (!paged && pf.any()) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (head < G) v = qp[4 * t + kg];
-            qb[t] = __builtin_bit_cast(bf16x8_t, v);
-        }
+        for (int t = 0; t < 4; ++t) qb[t] = pf.qb[t];
+        stage0_requested = pf.j0 == j0 && j0 + (wave + 1) * kMfBlockKeys <= j1;
+        if (!stage0_requested) wait_loads_landed();
+        pf.reset();
+    } else {
+        mfma_load_q(p, b, kvh, lane, qb);
     }
 
     // The wave's blocks are streamed in chunks: the whole range at once for a contiguous
@@ -294,19 +351,27 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             }
             mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
         };
-        for (int s = 0; s < P && s < cmine; ++s) issue(s);
+        for (int s = 0; s < P && s < cmine; ++s)
+            if (!(stage0_requested && c0 + s == 0)) issue(s);
         // Make the compiler wait for the q loads HERE: the loop below must contain no
         // compiler-generated vmcnt wait, which would also drain the stage loads the loop
         // keeps in flight (they are issued from inline asm, invisible to its counter).
         asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
-        for (int s = 0; s < cmine; ++s) {
+        // Only the range's last block can be ragged; it is the last block of the wave that owns it
+        // and is handled after the loop, which therefore holds the unmasked code alone.
+        const int kb_last = j0 + (wave + kWaves * (c0 + cmine - 1)) * kMfBlockKeys;
+        const int full = kb_last + kMfBlockKeys <= j1 ? cmine : cmine - 1;
+        for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kMfBlockKeys;
-            const char* stage = my_ring + (s % NST) * kMfStageBytes;
-            if (kb + kMfBlockKeys <= j1) mfma_consume_stage<false, F16>(stage, qb, st, sl2, kb, j1, lane);
-            else mfma_consume_stage<true, F16>(stage, qb, st, sl2, kb, j1, lane);
+            mfma_consume_stage<false, F16>(my_ring + (s % NST) * kMfStageBytes, qb, st, sl2, kb, j1, lane);
+        }
+        if (full < cmine) {
+            wait_stages_in_flight(0);
+            if (c0 + full == 0) trace_event(p, kEvFirstStage);
+            mfma_consume_stage<true, F16>(my_ring + (full % NST) * kMfStageBytes, qb, st, sl2, kb_last, j1, lane);
         }
     }
 

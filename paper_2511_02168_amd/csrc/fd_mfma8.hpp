@@ -30,20 +30,25 @@ constexpr int kM8HalfBytes = kM8BlockKeys * kM8RowBytes;    // K (or V) of a sta
 static_assert(2 * kM8HalfBytes == kMfStageBytes, "the FP8 stage reuses the bf16 kernel's ring");
 
 typedef int i32x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) i32x2_t* lds_i32x2_ptr;
 
 __device__ __forceinline__ int swz8(int r) { return (r ^ (r >> 2)) & 7; }
 
-// 8 E4M3 bytes (w.x = bytes 0..3, w.y = 4..7) -> 8 bf16, exactly
+// 8 E4M3 bytes (w.x = bytes 0..3, w.y = 4..7) -> 8 bf16, exactly: every E4M3 value is a bf16
+// value, and v_cvt_scalef32_pk_bf16_fp8 with scale 1 converts two bytes per instruction.
 __device__ __forceinline__ bf16x8_t fp8x8_to_bf16(i32x2_t w)
 {
-    const f32x2_t f01 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, false), f23 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, true);
-    const f32x2_t f45 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, false), f67 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, true);
+    typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+    const bf16x2_v a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, false);
+    const bf16x2_v b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, true);
+    const bf16x2_v c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, false);
+    const bf16x2_v d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, true);
     bf16x8_t r;
-    r[0] = (__bf16)f01[0]; r[1] = (__bf16)f01[1]; r[2] = (__bf16)f23[0]; r[3] = (__bf16)f23[1];
-    r[4] = (__bf16)f45[0]; r[5] = (__bf16)f45[1]; r[6] = (__bf16)f67[0]; r[7] = (__bf16)f67[1];
+    r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+    r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
     return r;
 }
 
@@ -106,22 +111,24 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
     float tm = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
     tm = fmaxf(tm, __shfl_xor(tm, 16));
     tm = fmaxf(tm, __shfl_xor(tm, 32));
-    const float mnew = fmaxf(st.m, tm);
-    if (__any(mnew > st.m)) {
+    // lazy reference maximum and hi + lo split as in mfma_consume_stage
+    if (__any(tm > st.m + kRescaleSlack)) {
+        const float mnew = fmaxf(st.m, tm);
         const float alpha = fast_exp2(st.m - mnew);
         st.m = mnew;
         st.l *= alpha;
 #pragma unroll
         for (int db = 0; db < 8; ++db) st.acc[db] *= alpha;
     }
-    bf16x8_t phi, plo;
+    s16x8_t phi, plo;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         p[e] = fast_exp2(p[e] - st.m);
         st.l += p[e];
-        const __bf16 hi = (__bf16)p[e];
-        phi[e] = hi;
-        plo[e] = (__bf16)(p[e] - (float)hi);
+        const uint32_t bits = __builtin_bit_cast(uint32_t, p[e]);
+        const __bf16 lo = (__bf16)(p[e] - __builtin_bit_cast(float, bits & 0xffff0000u));
+        phi[e] = (short)(bits >> 16);
+        plo[e] = __builtin_bit_cast(short, lo);
     }
 
     // a5: O^T[dim][head] += V^T . P^T over the 32 keys, 16 dims at a time
@@ -134,8 +141,25 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
     for (int db = 0; db < 8; ++db) {
         const i32x2_t w = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_ptr)(vrowp + ((db ^ vsw) << 4)));
         const bf16x8_t vt = fp8x8_to_bf16(w);
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, phi, st.acc[db], 0, 0, 0);
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, plo, st.acc[db], 0, 0, 0);
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, __builtin_bit_cast(bf16x8_t, phi), st.acc[db], 0, 0, 0);
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, __builtin_bit_cast(bf16x8_t, plo), st.acc[db], 0, 0, 0);
+    }
+}
+
+// mfma_prefetch for an FP8 cache: q and each wave's first 32-key block.
+template <int NST>
+__device__ __forceinline__ void mfma8_prefetch(const Params& p, int b, int kvh, int j0, int j1_max, char* ring,
+                                               MfmaPrefetch& pf)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    mfma_load_q(p, b, kvh, lane, pf.qb);
+    pf.j0 = j0;
+    const int kb = j0 + wave * kM8BlockKeys;
+    if (kb < j1_max) {
+        const size_t row = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max + (size_t)kb;
+        mfma8_issue_stage(lds_address(ring + wave * (NST * kMfStageBytes)), reinterpret_cast<const uint8_t*>(p.k) + row * kM8RowBytes,
+                          reinterpret_cast<const uint8_t*>(p.v) + row * kM8RowBytes, kb, j1_max, lane);
     }
 }
 
@@ -143,7 +167,7 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
 // PAGED as there (a 32-key block never straddles a page of 32 keys or more).
 template <int NST, bool PAGED, bool SHARED>
 __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
-                                  float lse_mul, char* ring)
+                                  float lse_mul, char* ring, MfmaPrefetch& pf)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -169,15 +193,17 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
     const float sl2 = p.scale_log2;
     constexpr int P = NST - 1;
 
+    // q and this wave's stage 0: from the prefetch if it aimed at this range (see mfma_item)
     bf16x8_t qb[4];
-    {
-        const uint4* qp = reinterpret_cast<const uint4*>(p.q) + ((size_t)b * p.Hq + (size_t)kvh * G + head) * kRowU4;
+    bool stage0_requested = false;
+    if (!PAGED && pf.any()) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (head < G) v = qp[4 * t + kg];
-            qb[t] = __builtin_bit_cast(bf16x8_t, v);
-        }
+        for (int t = 0; t < 4; ++t) qb[t] = pf.qb[t];
+        stage0_requested = pf.j0 == j0 && j0 + (wave + 1) * kM8BlockKeys <= j1;
+        if (!stage0_requested) wait_loads_landed();
+        pf.reset();
+    } else {
+        mfma_load_q(p, b, kvh, lane, qb);
     }
     // chunks of blocks as in mfma_item: one for a contiguous cache, kMfPageSlots blocks at a
     // time for a paged one, page numbers fetched into LDS while the pipeline is empty
@@ -206,17 +232,24 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
             }
             mfma8_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
         };
-        for (int s = 0; s < P && s < cmine; ++s) issue(s);
+        for (int s = 0; s < P && s < cmine; ++s)
+            if (!(stage0_requested && c0 + s == 0)) issue(s);
         // the compiler's wait for the q loads goes here, outside the loop (see mfma_item)
         asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
-        for (int s = 0; s < cmine; ++s) {
+        // the range's last block, if ragged, after the loop (see mfma_item)
+        const int kb_last = j0 + (wave + kWaves * (c0 + cmine - 1)) * kM8BlockKeys;
+        const int full = kb_last + kM8BlockKeys <= j1 ? cmine : cmine - 1;
+        for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kM8BlockKeys;
-            const char* stage = my_ring + (s % NST) * kMfStageBytes;
-            if (kb + kM8BlockKeys <= j1) mfma8_consume_stage<false>(stage, qb, st, sl2, kb, j1, lane);
-            else mfma8_consume_stage<true>(stage, qb, st, sl2, kb, j1, lane);
+            mfma8_consume_stage<false>(my_ring + (s % NST) * kMfStageBytes, qb, st, sl2, kb, j1, lane);
+        }
+        if (full < cmine) {
+            wait_stages_in_flight(0);
+            if (c0 + full == 0) trace_event(p, kEvFirstStage);
+            mfma8_consume_stage<true>(my_ring + (full % NST) * kMfStageBytes, qb, st, sl2, kb_last, j1, lane);
         }
     }
 

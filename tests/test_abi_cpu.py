@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_is_built_and_loads():
     assert os.path.exists(fd.LIB_PATH), "run `python -m paper_2511_02168_amd.build` first"
-    assert fd.fd_version() == 130
+    assert fd.fd_version() == 140
 
 
 def test_every_declared_symbol_is_exported():
@@ -91,3 +91,15 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2511_02168_amd" not in text and "libfd.so" not in text, f
+
+
+def test_host_computed_division_constants(tmp_path):
+    """csrc/fd_fastdiv.hpp (the multiply-high division of the kernels' work-list arithmetic), compiled for the
+    host and checked against the machine's own division: exhaustively for small operands, on boundary numerators
+    (multiples of the divisor and their neighbours, the top of the 31-bit range) for 200 000 seeded divisors."""
+    import subprocess
+    exe = tmp_path / "fastdiv_check"
+    src = os.path.join(ROOT, "tests", "fastdiv_check.cpp")
+    subprocess.run(["g++", "-O2", "-o", str(exe), src], check=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert res.returncode == 0 and res.stdout.startswith("OK"), res.stdout[-500:]

@@ -370,18 +370,22 @@ def test_xcd_grouping_and_grid_size_change_only_rounding():
     i.e. the summation order: results may differ by rounding only, and fused == BSP
     bitwise for every shape."""
     wl = fi.workload("c2")
-    say("case c2 (S reduced to 4096): XCD groups 1 vs 8, 1..4 workgroups per CU")
+    say("case c2 (S reduced to 4096): XCD groups 1 vs 8, 1 or 2 workgroups per CU")
     inp = fi.make_inputs(wl, "cuda", S_max=4096)
     ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
     with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, 4096, max_splits=16) as dec:
         for xg in (1, 8):
-            for per_cu in (1, 2, 4):
+            for per_cu in (1, 2):
                 fd.fd_set_option(dec.h, fd.FD_OPT_XCD_GROUPS, xg)
                 fd.fd_set_option(dec.h, fd.FD_OPT_WGS_PER_CU, per_cu)
                 fd.fd_debug_poison_workspace(dec.h)
                 out, lse = run_both(dec, inp, 16)
                 check_out(out, ref_o, f"xcd_groups={xg} wgs_per_cu={per_cu}")
                 check_lse(lse, ref_l, f"xcd_groups={xg} wgs_per_cu={per_cu}")
+        fd.fd_set_option(dec.h, fd.FD_OPT_WGS_PER_CU, 4)             # more than the MFMA kernel runs per CU: refused, not clamped
+        with pytest.raises(fd.FdError) as e:
+            dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+        assert e.value.code == fd.FD_ERR_INVALID_ARG
 
 
 def test_argument_errors_on_device():
