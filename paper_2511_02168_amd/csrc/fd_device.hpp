@@ -296,6 +296,39 @@ __device__ __forceinline__ float row16_max(float x)
     return x;
 }
 
+// Maximum / sum over the 4 lanes {i, i ^ 16, i ^ 32, i ^ 48} (in the MFMA kernels: the 4 key
+// groups of one query head), every one of them gets the result, with no trip through LDS.
+// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second;
+// fed the same value twice they return the two partners of every pair side by side.
+// Written as asm: through the compiler's builtins the max of the two results is folded away
+// (it takes them for equal).  The s_nop covers the wait states these instructions need after a
+// VALU write of their operands.
+__device__ __forceinline__ void rows_swap16(float& a, float& b)
+{
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void rows_swap32(float& a, float& b)
+{
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float head_lanes_max(float x)
+{
+    float a = x, b = x;
+    rows_swap16(a, b);
+    a = b = fmaxf(a, b);
+    rows_swap32(a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float head_lanes_sum(float x)
+{
+    float a = x, b = x;
+    rows_swap16(a, b);
+    a = b = a + b;
+    rows_swap32(a, b);
+    return a + b;
+}
+
 // ---- end of an item: merge the workgroup's 4 wave states, normalise, store ------
 // Each wave leaves its running max m, sum l and unnormalised accumulator for the
 // ROWS query heads of the tile here; all in base-2 units.
@@ -358,10 +391,15 @@ constexpr int kMaxSplits = 1024;
 constexpr int kCombineWCap = 4096;     // weights staged in LDS: heads x (live rows, padded)
 constexpr int kCombineGroup = 8;       // rows are loaded and padded in groups of this many
 
-struct CombineSmem {
-    // live slots in ascending order, row k at [(k % R) * stride + k / R] (R row slices, see below)
+// The slots of a tile that hold a partial, in ascending order: row k at
+// [(k % R) * stride + k / R] (R row slices, see combine_tile).  Kept apart from the combine's
+// scratch: the fused kernel fills it while its K/V ring (which the scratch overlays) is in use.
+struct LiveList {
     int live[kMaxSplits + 8 * 32];
-    int n_live, live0;
+    int n_live;
+};
+
+struct CombineSmem {
     float w[kCombineWCap];      // exp2(lse - max) of row k of head g at [((g * R) + k % R) * KJ + k / R], 0 in the padding
     float invL[16];             // per head
     float4 red[kWgThreads];     // cross-slice reduction
@@ -433,7 +471,7 @@ __device__ __forceinline__ int combine_live_stride(int log_r) { return (kMaxSpli
 
 // Pads the live list to whole row groups (the padding re-reads the first live row with weight 0)
 // and publishes the count.  Wave 0 only.
-__device__ __forceinline__ void combine_live_finish(CombineSmem& sm, int count, int live0, int log_r, int lane)
+__device__ __forceinline__ void combine_live_finish(LiveList& sm, int count, int live0, int log_r, int lane)
 {
     const int R = 1 << log_r, stride = combine_live_stride(log_r);
     for (int k = count + lane; k < count + R * (kCombineGroup + 1); k += 64)
@@ -442,9 +480,9 @@ __device__ __forceinline__ void combine_live_finish(CombineSmem& sm, int count, 
 }
 
 // The live slots of a tile of the fused kernel follow from the schedule: no memory access.
-// Wave 0 only (all 64 lanes).  It does not depend on anything another workgroup does, so the
-// fused kernel runs it while its arrival count is still on its way back from memory.
-__device__ inline void combine_live_from_schedule(CombineSmem& sm, const TileSchedule& sch, int n, int G)
+// Wave 0 only (all 64 lanes).  It depends on nothing another workgroup does, so the fused kernel
+// runs it early, while the wave would otherwise wait for K/V data in flight.
+__device__ inline void combine_live_from_schedule(LiveList& sm, const TileSchedule& sch, int n, int G)
 {
     const int lane = threadIdx.x & 63;
     const int log_r = combine_log_r(G), R = 1 << log_r, stride = combine_live_stride(log_r);
@@ -475,7 +513,7 @@ __device__ inline void combine_live_from_schedule(CombineSmem& sm, const TileSch
 // live_ready: the live list is already in sm (combine_live_from_schedule); otherwise wave 0
 // finds the live slots by reading head 0's lse of every slot.
 template <int BATCH>
-__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm,
+__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm, LiveList& ll,
                                     bool live_ready = false)
 {
     static_assert(BATCH % kCombineGroup == 0 && BATCH <= 32, "row batch");
@@ -513,18 +551,18 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
                     const bool live = first[j] != -INFINITY;
                     const unsigned long long mask = __ballot(live);
                     const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
-                    if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
+                    if (live) ll.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
                     if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
                     count += __popcll(mask);
                 }
             }
         }
-        combine_live_finish(sm, count, live0, log_r, lane);
+        combine_live_finish(ll, count, live0, log_r, lane);
     }
     trace_event(p, kEvCombA);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     __syncthreads();
-    const int n_live = sm.n_live;
+    const int n_live = ll.n_live;
     trace_event(p, kEvCombB);
     if (n_live == 0) {                                   // no key anywhere in the tile
         for (int i = tid; i < G * kD; i += kWgThreads) out_rows[i] = 0.f;
@@ -535,7 +573,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     // rows per slice, padded to whole groups
     const int KJ = (((n_live + R - 1) >> log_r) + kCombineGroup - 1) & ~(kCombineGroup - 1);
     if (G * R * KJ > kCombineWCap) {
-        combine_tile_unstaged(plse, po, out_rows, lse_rows, G, n_live, sm.live, log_r, stride);
+        combine_tile_unstaged(plse, po, out_rows, lse_rows, G, n_live, ll.live, log_r, stride);
         __syncthreads();
         return;
     }
@@ -545,13 +583,13 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     const int pair0 = tid - slice * kPairs;
     const size_t row_f4 = (size_t)G * (kD / 4);          // float4 per slot
     const float4* po4 = reinterpret_cast<const float4*>(po);
-    const int* my_live = &sm.live[slice * stride];
+    const int* my_live = &ll.live[slice * stride];
 
     // weights: 16 lanes per head, lane j takes rows j, j+16, ...  The lse loads of the first
     // 64 rows go out BEFORE the row loads, so that the weights do not wait for the rows.
     const bool stat_lane = (tid >> 4) < G;
     const int sg = tid >> 4, sj = tid & 15;
-    const auto live_at = [&](int k) { return sm.live[(k & (R - 1)) * stride + (k >> log_r)]; };
+    const auto live_at = [&](int k) { return ll.live[(k & (R - 1)) * stride + (k >> log_r)]; };
     float v[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {

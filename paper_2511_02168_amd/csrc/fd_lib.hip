@@ -43,10 +43,11 @@ struct ValuPath {
     static constexpr bool kPrefetch = false;
     ItemSmem<G>* sm;
     __device__ __forceinline__ void prefetch(const Params&, int, int, int, int, MfmaPrefetch&) const {}
-    template <bool SHARED>
+    template <bool SHARED, class Hook>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
-                                         float mul, MfmaPrefetch&) const
+                                         float mul, MfmaPrefetch&, const Hook& hook) const
     {
+        if (threadIdx.x < 64) hook();
         valu_item<G, SHARED>(p, b, kvh, j0, j1, o, l, mul, *sm);
     }
 };
@@ -61,11 +62,11 @@ struct MfmaPath {
     {
         mfma_prefetch<NST>(p, b, kvh, j0, j1_max, ring, pf);
     }
-    template <bool SHARED>
+    template <bool SHARED, class Hook>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
-                                         float mul, MfmaPrefetch& pf) const
+                                         float mul, MfmaPrefetch& pf, const Hook& hook) const
     {
-        mfma_item<NST, PAGED, F16, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring, pf);
+        mfma_item<NST, PAGED, F16, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring, pf, hook);
     }
 };
 
@@ -77,11 +78,11 @@ struct Mfma8Path {
     {
         mfma8_prefetch<NST>(p, b, kvh, j0, j1_max, ring, pf);
     }
-    template <bool SHARED>
+    template <bool SHARED, class Hook>
     __device__ __forceinline__ void item(const Params& p, int b, int kvh, int j0, int j1, float* o, float* l,
-                                         float mul, MfmaPrefetch& pf) const
+                                         float mul, MfmaPrefetch& pf, const Hook& hook) const
     {
-        mfma8_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring, pf);
+        mfma8_item<NST, PAGED, SHARED>(p, b, kvh, j0, j1, o, l, mul, ring, pf, hook);
     }
 };
 
@@ -89,6 +90,7 @@ struct SchedSmem {
     int pre[kMaxGroupTiles + 1];
     int scan_tmp[kWgThreads];
     int is_last;
+    LiveList live;
 };
 
 // What a workgroup does after a partial: nothing (kernel 1 of the bulk-synchronous
@@ -158,7 +160,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             float* o = p.out + ((size_t)it.b * p.Hq + (size_t)it.kvh * G) * kD;
             float* l = p.lse ? p.lse + (size_t)it.b * p.Hq + it.kvh * G : nullptr;
             if (j0 < j1) {
-                path.template item<false>(p, it.b, it.kvh, j0, j1, o, l, kLn2, pf);
+                path.template item<false>(p, it.b, it.kvh, j0, j1, o, l, kLn2, pf, [] {});
             } else {                         // empty sequence: out = 0, lse = -inf
                 for (int i = threadIdx.x; i < G * kD; i += kWgThreads) o[i] = 0.f;
                 if (l && threadIdx.x < G) l[threadIdx.x] = -INFINITY;
@@ -176,8 +178,19 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
 
         // a6: one partial for the run in its first slot; the run's other slots (and
         // the first one too if the run has no keys) are marked empty
+        // a8, first part: which of the tile's slots will hold a partial follows from the schedule;
+        // wave 0 lists them while it would otherwise wait for its first K/V stages (in case this
+        // workgroup turns out to be the tile's last arriver).
+        const auto list_live = [&] {
+            if (MODE == kModeFused) {
+                const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
+                combine_live_from_schedule(ss.live, sch, it.n, G);
+            }
+        };
         if (j0 < j1)
-            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f, pf);
+            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f, pf, list_live);
+        else if (threadIdx.x < 64)
+            list_live();
         {
             const int skip = j0 < j1 ? G : 0;
             for (int i = skip + threadIdx.x; i < run * G; i += kWgThreads)
@@ -189,24 +202,18 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             // a7: the partial went out with coherent stores; once they are acknowledged
             // and every wave has reached the barrier, one thread counts the run's splits
             // as arrived (Algorithm 4: push, then atomic increment of the flag).
-            // a8: whoever completes the tile's count combines it.  While the count is on its
-            // way back, wave 0 already lists the tile's live slots from the schedule (wasted
-            // on every workgroup but the last, which have nothing else to do then).
+            // a8: whoever completes the tile's count combines it.
             wait_stores_done();
             trace_event(p, kEvStoresAcked);
             __syncthreads();
             uint32_t old = 0;
             if (threadIdx.x == 0)
                 old = __hip_atomic_fetch_add(&p.counters[it.tile], (uint32_t)run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (MODE == kModeFused && threadIdx.x < 64) {
-                const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
-                combine_live_from_schedule(comb, sch, it.n, G);
-            }
             if (threadIdx.x == 0) ss.is_last = old + (uint32_t)run == (uint32_t)it.n;
             __syncthreads();
             trace_event(p, kEvCounted);
             if (MODE == kModeFused && ss.is_last) {
-                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, true);
+                combine_tile<COMB_BATCH>(p, it.tile, it.b, it.kvh, it.n, comb, ss.live, true);
                 if (threadIdx.x == 0)                               // re-arm for the next call
                     __hip_atomic_store(&p.counters[it.tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 trace_event(p, kEvCombined);
@@ -266,6 +273,7 @@ __global__ __launch_bounds__(kWgThreads, 1) void fd_mfma_signal_kernel(Params p)
 __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
 {
     __shared__ CombineSmem sm;
+    __shared__ LiveList ll;
     __shared__ uint32_t done;
     const int tile = blockIdx.x;
     const int b = tile / p.Hkv, kvh = tile - b * p.Hkv;
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
     __syncthreads();
     if (done) return;
     trace_event(p, kEvStart);
-    combine_tile<32>(p, tile, b, kvh, n, sm);
+    combine_tile<32>(p, tile, b, kvh, n, sm, ll);
     trace_event(p, kEvEnd);
 }
 
@@ -294,6 +302,7 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
 __global__ __launch_bounds__(kWgThreads, 4) void fd_combine_wait_kernel(Params p)
 {
     __shared__ CombineSmem sm;
+    __shared__ LiveList ll;
     __shared__ uint32_t seen;
     const int tiles = p.B * p.Hkv;
     for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
@@ -315,7 +324,7 @@ __global__ __launch_bounds__(kWgThreads, 4) void fd_combine_wait_kernel(Params p
             if (threadIdx.x == 0) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
-        if (c != kTileDirect) combine_tile<8>(p, tile, b, kvh, (int)n, sm);
+        if (c != kTileDirect) combine_tile<8>(p, tile, b, kvh, (int)n, sm, ll);
         if (threadIdx.x == 0)              // re-arm for the next call
             __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

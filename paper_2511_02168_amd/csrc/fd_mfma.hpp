@@ -165,8 +165,7 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
         if (MASKED) p[e] = (kb + 4 * kg + e) < j1 ? p[e] : -INFINITY;
     }
     float tm = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3]));
-    tm = fmaxf(tm, __shfl_xor(tm, 16));
-    tm = fmaxf(tm, __shfl_xor(tm, 32));
+    tm = head_lanes_max(tm);
     // The reference maximum st.m only moves when some head's scores exceed it by more than
     // kRescaleSlack (then every head moves to its current maximum): weights stay below
     // 2^kRescaleSlack, which fp32 sums and the hi + lo split below carry without loss, and the
@@ -268,9 +267,12 @@ __device__ __forceinline__ void mfma_prefetch(const Params& p, int b, int kvh, i
 // it doubles as the ItemSmem<16> staging at the end of the range.
 // Writes the normalised result to dst_o[G][D] and the log-sum-exp times lse_mul to
 // dst_lse[G] (SHARED as in item_finish).  Leaves LDS free for reuse on return.
-template <int NST, bool PAGED, bool F16, bool SHARED>
+// pf: what mfma_prefetch requested for this range, if anything (reset here).  hook: a side job
+// of the caller that touches no global memory; wave 0 runs it once, right after its first
+// requests of the loop have gone out, in time the wave would spend waiting for them.
+template <int NST, bool PAGED, bool F16, bool SHARED, class Hook>
 __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
-                                 float lse_mul, char* ring, MfmaPrefetch& pf)
+                                 float lse_mul, char* ring, MfmaPrefetch& pf, const Hook& hook)
 {
     static_assert(NST >= 2 && NST <= 8, "ring depth");
     static_assert(sizeof(ItemSmem<kMfRows>) <= (size_t)mfma_ring_bytes(2), "staging must fit the ring");
@@ -363,12 +365,15 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
         const int full = kb_last + kMfBlockKeys <= j1 ? cmine : cmine - 1;
         for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
+            // the caller's side job, once, by wave 0, with this wave's requests in flight
+            if (c0 + s == 0 && wave == 0) hook();
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kMfBlockKeys;
             mfma_consume_stage<false, F16>(my_ring + (s % NST) * kMfStageBytes, qb, st, sl2, kb, j1, lane);
         }
         if (full < cmine) {
+            if (c0 + full == 0 && wave == 0) hook();
             wait_stages_in_flight(0);
             if (c0 + full == 0) trace_event(p, kEvFirstStage);
             mfma_consume_stage<true, F16>(my_ring + (full % NST) * kMfStageBytes, qb, st, sl2, kb_last, j1, lane);
@@ -377,8 +382,7 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
 
     trace_event(p, kEvLoopEnd);
     // a6: every lane of a head gets the head's sum; then the wave leaves its state in LDS
-    st.l += __shfl_xor(st.l, 16);
-    st.l += __shfl_xor(st.l, 32);
+    st.l = head_lanes_sum(st.l);
     __syncthreads();                                      // all waves are done reading their rings
     ItemSmem<kMfRows>& sm = *reinterpret_cast<ItemSmem<kMfRows>*>(ring);
     if (head < G) {

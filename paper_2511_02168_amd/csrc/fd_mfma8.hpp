@@ -109,8 +109,7 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
             p[4 * blk + e] = x;
         }
     float tm = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
-    tm = fmaxf(tm, __shfl_xor(tm, 16));
-    tm = fmaxf(tm, __shfl_xor(tm, 32));
+    tm = head_lanes_max(tm);
     // lazy reference maximum and hi + lo split as in mfma_consume_stage
     if (__any(tm > st.m + kRescaleSlack)) {
         const float mnew = fmaxf(st.m, tm);
@@ -165,9 +164,9 @@ __device__ __forceinline__ void mfma8_prefetch(const Params& p, int b, int kvh, 
 
 // Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) of an FP8 cache; contract as mfma_item,
 // PAGED as there (a 32-key block never straddles a page of 32 keys or more).
-template <int NST, bool PAGED, bool SHARED>
+template <int NST, bool PAGED, bool SHARED, class Hook>
 __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
-                                  float lse_mul, char* ring, MfmaPrefetch& pf)
+                                  float lse_mul, char* ring, MfmaPrefetch& pf, const Hook& hook)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -241,12 +240,15 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
         const int full = kb_last + kM8BlockKeys <= j1 ? cmine : cmine - 1;
         for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
+            // the caller's side job, once, by wave 0, with this wave's requests in flight
+            if (c0 + s == 0 && wave == 0) hook();
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kM8BlockKeys;
             mfma8_consume_stage<false>(my_ring + (s % NST) * kMfStageBytes, qb, st, sl2, kb, j1, lane);
         }
         if (full < cmine) {
+            if (c0 + full == 0 && wave == 0) hook();
             wait_stages_in_flight(0);
             if (c0 + full == 0) trace_event(p, kEvFirstStage);
             mfma8_consume_stage<true>(my_ring + (full % NST) * kMfStageBytes, qb, st, sl2, kb_last, j1, lane);
@@ -254,8 +256,7 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
     }
 
     trace_event(p, kEvLoopEnd);
-    st.l += __shfl_xor(st.l, 16);
-    st.l += __shfl_xor(st.l, 32);
+    st.l = head_lanes_sum(st.l);
     __syncthreads();                                      // all waves are done reading their rings
     ItemSmem<kMfRows>& sm = *reinterpret_cast<ItemSmem<kMfRows>*>(ring);
     if (head < G) {
