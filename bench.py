@@ -37,7 +37,8 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="rotating K/V copies (0 = enough to exceed 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bsp", action="store_true")
-    ap.add_argument("--waits", action="store_true", help="also time the fine-grained-waits variant (fd_decode_waits)")
+    ap.add_argument("--no-waits", action="store_true", help="skip the fine-grained-waits variant (fd_decode_waits)")
+    ap.add_argument("--no-hot", action="store_true", help="skip the hot-cache figure (one K/V copy) of the workloads that fit the Infinity Cache")
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only streaming kernel (achievable bandwidth)")
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
@@ -104,21 +105,28 @@ def streaming_probe(fd, torch, stream):
     return gbs
 
 
-def read_traffic(workload_name):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"fd_fused_{workload_name}_pmc.txt")
+def read_traffic(workload_name, dtype, page_size):
+    """HBM bytes per launch of the fused kernel from the committed rocprofv3 --pmc summary of THIS workload, element
+    type and cache layout, or None if there is none.  Warns when the summary is older than the kernel sources."""
+    tag = ("" if dtype == "bf16" else f"_{dtype}") + (f"_page{page_size}" if page_size else "")
+    path = os.path.join(ROOT, "profiles", f"fd_fused{tag}_{workload_name}_pmc.txt")
     if not os.path.exists(path):
         return None
+    csrc = os.path.join(ROOT, "paper_2511_02168_amd", "csrc")
+    newest = max(os.path.getmtime(os.path.join(csrc, f)) for f in os.listdir(csrc))
+    if os.path.getmtime(path) < newest:
+        print(f"bench.py: warning: {os.path.relpath(path, ROOT)} is older than the kernel sources; "
+              "roofline.traffic may be stale", file=sys.stderr)
     m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(inp, wl, fi, fmt="bf16"):
-    """The fp64 oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+def cpu_baseline(inp, wl, fi, fmt="bf16", n_threads=0, seconds=10.0):
+    """The fp64 oracle as it stands, timed on the host cores (n_threads = 0: all of them) on a bounded sample."""
     import numpy as np
     import oracle
-    # sample: whole sequences of the first sequences / heads, sized to ~1e10 multiply-adds at most
-    budget_keys_heads = 6.0e7 * 4            # (keys x query heads) the oracle gets through in ~10-30 s
+    # sample: whole sequences of the first sequences / heads, sized to what the oracle gets through in ~10-30 s
+    budget_keys_heads = 6.0e7 * 4 if n_threads == 0 else 2.0e7
     sl = inp.seq_lens.cpu().numpy()
     B = 0
     acc = 0
@@ -130,13 +138,13 @@ def cpu_baseline(inp, wl, fi, fmt="bf16"):
     t0 = time.perf_counter()
     reps = 0
     while True:
-        oracle.decode(q, k, v, sl[:B], fmt=fmt)
+        oracle.decode(q, k, v, sl[:B], fmt=fmt, n_threads=n_threads)
         reps += 1
-        if time.perf_counter() - t0 > 10.0 or reps >= 20:
+        if time.perf_counter() - t0 > seconds or reps >= 20:
             break
     dt = (time.perf_counter() - t0) / reps
     nbytes = fi.algorithmic_bytes(wl, sl[:B])
-    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": int(oracle.max_threads()),
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": int(n_threads or oracle.max_threads()),
             "kind": "oracle", "us_per_call": round(dt * 1e6, 1),
             "sample": f"first {B} of {wl.B} sequences, all {wl.Hq} query heads, full length "
                       f"({int(sl[:B].sum())} keys), {reps} runs, mean"}
@@ -214,7 +222,8 @@ def main():
         fd.fd_autotune(dec.h, inp.q, ks[0], vs[0], inp.seq_lens, out, lse, wl.n_splits, stream, reps=30)
         tuned = {"path": fd.fd_get_option(dec.h, fd.FD_OPT_PATH), "xcd_groups": fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS),
                  "wgs_per_cu": fd.fd_get_option(dec.h, fd.FD_OPT_WGS_PER_CU),
-                 "ring_stages": fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES)}
+                 "ring_stages": fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES),
+                 "adaptive_split_keys": fd.fd_get_option(dec.h, fd.FD_OPT_SPLIT_KEYS) if wl.n_splits == 0 else None}
     fused_ms, fused_wall_ms = time_calls(fused, args.warmup, args.steps, torch)
     grid = fd.fd_get_option(dec.h, fd.FD_INFO_LAST_GRID)
     path = fd.fd_get_option(dec.h, fd.FD_INFO_LAST_PATH)
@@ -223,13 +232,17 @@ def main():
         bsp_ms, _ = time_calls(bsp, args.warmup, args.steps, torch)
 
     waits_ms = None
-    if args.waits and not args.page_size and path == 2 and args.dtype == "bf16":
+    if not args.no_waits and not args.page_size and path == 2 and args.dtype == "bf16":
         def waits(i):
             j = i % copies
             fd.fd_decode_waits(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
         waits_ms, _ = time_calls(waits, args.warmup, args.steps, torch)
         if fd.fd_get_option(dec.h, fd.FD_INFO_WAIT_GAVE_UP):
             waits_ms = None
+    # hot cache: one K/V copy, for the workloads whose K/V fit the 256 MB Infinity Cache
+    hot_ms = None
+    if not args.no_hot and copies > 1 and kv_bytes <= (256 << 20):
+        hot_ms, _ = time_calls(lambda i: fused(0), args.warmup, args.steps, torch)
     pct_fused = per_call_percentiles(fused, min(args.steps, 200), torch)
     pct_bsp = None if args.no_bsp else per_call_percentiles(bsp, min(args.steps, 200), torch)
     probe_gbs = None if args.no_probe else streaming_probe(fd, torch, stream)
@@ -248,7 +261,8 @@ def main():
         "vs_baseline": None,
         "dtype": args.dtype,
         "dtype_detail": f"{args.dtype} q/K/V, products and sums in f32 (MFMA f32 accumulate), f32 out and lse",
-        "data": "synthetic (seeded N(0,1) q/K/V rounded to bf16; ragged lengths, scaled K and aligned keys per workload)",
+        "data": "synthetic (seeded N(0,1) q/K/V rounded to " + {"bf16": "bf16", "fp16": "IEEE half", "fp8kv": "bf16, K/V then to E4M3 bytes with scale 1/32"}[args.dtype]
+                + "; ragged lengths, scaled K and aligned keys per workload)",
         "config": {"workload": wl.name, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "S_max": wl.S_max,
                    "n_splits": wl.n_splits, "total_keys": int(sl_host.sum()), "kv_copies_rotated": copies,
                    "kv_layout": f"paged, page_size {args.page_size}, random placement" if args.page_size else "contiguous",
@@ -257,6 +271,7 @@ def main():
         "us_per_call_fused_host_wall": round(fused_wall_ms * 1e3, 3),
         "us_per_call_bsp": None if bsp_ms is None else round(bsp_ms * 1e3, 3),
         "us_per_call_fine_grained_waits": None if waits_ms is None else round(waits_ms * 1e3, 3),
+        "us_per_call_fused_hot_cache": None if hot_ms is None else round(hot_ms * 1e3, 3),
         "fused_over_bsp": None if bsp_ms is None else round(fused_ms / bsp_ms, 4),
         "us_single_call_fused_p10_p50_p90": pct_fused,
         "us_single_call_bsp_p10_p50_p90": pct_bsp,
@@ -265,11 +280,13 @@ def main():
         "pct_of_hbm_roofline": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_call": alg_bytes,
         "roofline": {"bound": "hbm", "achieved": round(gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name, args.dtype, args.page_size),
                      "kernel": "fd fused persistent kernel (one launch per call)"},
     }
     if not args.no_cpu_baseline and not fp8:
         rec["cpu_baseline"] = cpu_baseline(inp, wl, fi, args.dtype)
+        if wl.index <= 2:                     # the small workloads also on one core
+            rec["cpu_baseline_1core"] = cpu_baseline(inp, wl, fi, args.dtype, n_threads=1, seconds=5.0)
     dec.close()
     print(json.dumps(rec))
 

@@ -297,8 +297,16 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
 // polls the tile's arrival counter with coherent loads until the count is complete, the
 // other waves sleep at the barrier.  Kernel 1 never waits for anything, so the counts always
 // complete; the poll is bounded all the same (p.spin_limit): a workgroup that gives up sets
-// *p.status and leaves its remaining tiles alone.  Capped at 128 registers so that it fits
-// beside a workgroup of kernel 1 on every SIMD.
+// *p.status and leaves its remaining tiles alone.
+// Sharing a CU with kernel 1: the waiting workgroup is capped at 128 registers per lane (kernel 1
+// needs at most 360 of a SIMD's 512) and is launched with kWaitPadLds bytes of LDS it never
+// touches: with them one waiter (its own 22 KB + the padding) fits beside a workgroup of
+// kernel 1 (83 KB) in the CU's 160 KB, two waiters do not, so a compute unit never hosts more
+// than one of them while kernel 1 is resident.  Correctness does not depend on it (kernel 1
+// never waits); it keeps the waiters from crowding kernel 1 out of LDS.
+constexpr int kWaitPadLds = 24 * 1024;
+static_assert(sizeof(CombineSmem) + sizeof(LiveList) + kWaitPadLds + 85 * 1024 <= 160 * 1024, "one waiter beside kernel 1");
+static_assert(2 * (sizeof(CombineSmem) + sizeof(LiveList) + kWaitPadLds) + 80 * 1024 > 160 * 1024, "never two waiters beside kernel 1");
 __global__ __launch_bounds__(kWgThreads, 4) void fd_combine_wait_kernel(Params p)
 {
     __shared__ CombineSmem sm;
@@ -555,7 +563,7 @@ int launch_waits(fd_handle_t h, const fd::Params& p, int grid, hipStream_t st)
     FD_HIP(hipStreamWaitEvent(h->side_stream, h->ev_fork, 0));
     hipLaunchKernelGGL(fd::fd_mfma_signal_kernel, dim3(grid), dim3(fd::kWgThreads), lds, st, p);
     FD_HIP(hipGetLastError());
-    hipLaunchKernelGGL(fd::fd_combine_wait_kernel, dim3(waiters), dim3(fd::kWgThreads), 0, h->side_stream, p);
+    hipLaunchKernelGGL(fd::fd_combine_wait_kernel, dim3(waiters), dim3(fd::kWgThreads), fd::kWaitPadLds, h->side_stream, p);
     FD_HIP(hipGetLastError());
     FD_HIP(hipEventRecord(h->ev_join, h->side_stream));
     FD_HIP(hipStreamWaitEvent(st, h->ev_join, 0));

@@ -561,7 +561,8 @@ def test_autotune_leaves_valid_options_and_results():
             assert fd.fd_get_option(dec.h, fd.FD_OPT_PATH) in (1, 2)
             assert fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS) in (1, 8)
             say(f"  chose path {fd.fd_get_option(dec.h, fd.FD_OPT_PATH)} lists {fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS)} "
-                f"per CU {fd.fd_get_option(dec.h, fd.FD_OPT_WGS_PER_CU)} ring {fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES)}: {us:.1f} us")
+                f"per CU {fd.fd_get_option(dec.h, fd.FD_OPT_WGS_PER_CU)} ring {fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES)} "
+                f"split keys {fd.fd_get_option(dec.h, fd.FD_OPT_SPLIT_KEYS)}: {us:.1f} us")
             check_out(out.cpu().numpy(), ref_o, "autotune result")        # the last timed call's result is valid
             check_lse(lse.cpu().numpy(), ref_l, "autotune result")
             out2, lse2 = run_both(dec, inp, 0)
@@ -569,6 +570,77 @@ def test_autotune_leaves_valid_options_and_results():
             check_lse(lse2, ref_l, "after autotune")
             with pytest.raises(fd.FdError) as e:
                 fd.fd_autotune(dec.h, inp.q, inp.k, inp.v, inp.seq_lens, out, lse, 0, reps=0)
+            assert e.value.code == fd.FD_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "fp8kv"])
+def test_autotune_on_half_and_fp8_handles(dtype):
+    """fd_autotune builds its candidates from what the handle's element type is built for (no VALU kernel, no
+    deeper rings for half; the MFMA kernel only for FP8) and skips combinations a shape does not allow."""
+    wl = _generic(4, 16, 4, 3000, 810, ragged=True)            # G = 4
+    say(f"case fd_autotune on a {dtype} handle, G=4")
+    ks = vs = 1.0 / 32
+    if dtype == "fp16":
+        inp = fi.make_inputs(wl, "cuda", dtype=torch.float16)
+        k, v = inp.k, inp.v
+        ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(k), fi.bits(v), inp.seq_lens.cpu().numpy(), fmt="fp16")
+    else:
+        inp = fi.make_inputs(wl, "cuda")
+        k, v = fi.to_fp8_cache(inp, ks, vs)
+        ref_o, ref_l = oracle.decode_fp8kv(fi.bits(inp.q), fi.bytes_of(k), fi.bytes_of(v), inp.seq_lens.cpu().numpy(),
+                                           k_scale=ks, v_scale=vs)
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=16, dtype=dtype, k_scale=ks, v_scale=vs) as dec:
+        out = torch.empty(wl.B, wl.Hq, 128, device="cuda")
+        lse = torch.empty(wl.B, wl.Hq, device="cuda")
+        for n in (0, 6):
+            us = fd.fd_autotune(dec.h, inp.q, k, v, inp.seq_lens, out, lse, n, reps=5)
+            assert us > 0 and fd.fd_get_option(dec.h, fd.FD_OPT_PATH) == 2
+            say(f"  n={n}: lists {fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS)} per CU {fd.fd_get_option(dec.h, fd.FD_OPT_WGS_PER_CU)} "
+                f"ring {fd.fd_get_option(dec.h, fd.FD_OPT_RING_STAGES)} split keys {fd.fd_get_option(dec.h, fd.FD_OPT_SPLIT_KEYS)}: {us:.1f} us")
+            check_out(out.cpu().numpy(), ref_o, f"autotune {dtype} n={n}")
+            check_lse(lse.cpu().numpy(), ref_l, f"autotune {dtype} n={n}")
+            out2, lse2 = dec.decode(inp.q, k, v, inp.seq_lens, n)
+            torch.cuda.synchronize()
+            check_out(out2.cpu().numpy(), ref_o, f"after autotune {dtype} n={n}")
+            check_lse(lse2.cpu().numpy(), ref_l, f"after autotune {dtype} n={n}")
+
+
+def test_autotune_skips_what_a_shape_does_not_allow():
+    """More than 2048 tiles with adaptive splits: one work list is not built for that (FD_ERR_UNSUPPORTED), eight
+    lists are; the search must skip the former, not fail."""
+    wl = _generic(2056, 1, 1, 64, 820)
+    say("case fd_autotune with 2056 tiles, adaptive splits")
+    inp = fi.make_inputs(wl, "cuda")
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=2) as dec:
+        out = torch.empty(wl.B, wl.Hq, 128, device="cuda")
+        lse = torch.empty(wl.B, wl.Hq, device="cuda")
+        us = fd.fd_autotune(dec.h, inp.q, inp.k, inp.v, inp.seq_lens, out, lse, 0, reps=3)
+        assert us > 0 and fd.fd_get_option(dec.h, fd.FD_OPT_XCD_GROUPS) == 8
+        check_out(out.cpu().numpy(), ref_o, "autotune 2056 tiles")
+        check_lse(lse.cpu().numpy(), ref_l, "autotune 2056 tiles")
+
+
+@pytest.mark.parametrize("keys", [64, 256, 1024, 4096])
+def test_adaptive_split_granularity_option(keys):
+    """FD_OPT_SPLIT_KEYS: how finely a tile is cut when the library picks the split count (the granularity
+    axis of the autotune).  Any value changes only the partition, i.e. rounding."""
+    wl = _generic(6, 16, 2, 9000, 830 + keys, ragged=True)
+    say(f"case adaptive splits of {keys} keys, G=8, ragged S<=9000")
+    inp = fi.make_inputs(wl, "cuda")
+    ref_o, ref_l = oracle.decode(fi.bits(inp.q), fi.bits(inp.k), fi.bits(inp.v), inp.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=64) as dec:
+        fd.fd_set_option(dec.h, fd.FD_OPT_SPLIT_KEYS, keys)
+        assert fd.fd_get_option(dec.h, fd.FD_OPT_SPLIT_KEYS) == keys
+        for xg in (1, 8) if (wl.B * wl.Hkv) % 8 == 0 else (1,):
+            fd.fd_set_option(dec.h, fd.FD_OPT_XCD_GROUPS, xg)
+            fd.fd_debug_poison_workspace(dec.h)
+            out, lse = run_both(dec, inp, 0)
+            check_out(out, ref_o, f"split keys {keys} lists {xg}")
+            check_lse(lse, ref_l, f"split keys {keys} lists {xg}")
+        for bad in (32, 100, 65600, -64):
+            with pytest.raises(fd.FdError) as e:
+                fd.fd_set_option(dec.h, fd.FD_OPT_SPLIT_KEYS, bad)
             assert e.value.code == fd.FD_ERR_INVALID_ARG
 
 
