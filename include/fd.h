@@ -48,7 +48,7 @@ enum {
     FD_ERR_HIP = -4          /* a HIP runtime call failed (no device, launch error)          */
 };
 
-/* Keys per split used when the library picks the split count itself. */
+/* Keys per split used when the library picks the split count itself (FD_OPT_SPLIT_KEYS = 0). */
 #define FD_ADAPTIVE_SPLIT_KEYS 512
 /* Upper bound accepted for fd_config.max_splits. */
 #define FD_MAX_SPLITS 1024
@@ -94,7 +94,8 @@ typedef struct {
 #define FD_DTYPE_FP16 1
 #define FD_DTYPE_FP8_KV 2
 
-/* Bytes of device workspace fd_create() allocates for cfg (0 if cfg is invalid). */
+/* Bytes of device workspace (Algorithm 4's inbox and flags for this shape) fd_create() allocates
+ * for cfg (0 if cfg is invalid). */
 size_t fd_workspace_bytes(const fd_config* cfg);
 
 /*
@@ -102,16 +103,23 @@ size_t fd_workspace_bytes(const fd_config* cfg);
  * [B,Hkv,max_splits,G,D] fp32, their LSEs, one arrival counter per tile), zeroes
  * the counters, and creates the stream and two events fd_decode_waits uses.
  * Synchronous.  *out receives the handle.
+ * The workspace stands for Algorithm 4's inbox and signal flags.  The paper gives the problem
+ * only as the inputs of Algorithm 4 (query, KV shard) and has no interface; a handle that fixes
+ * the shape and owns inbox and flags is this library's reading.  The paper is also silent on how
+ * the flags are re-armed between the calls of its timing loop (Section 5.1); here they start at
+ * zero (this call) and the workgroup that merges a tile stores zero back, so that every
+ * completed call leaves them ready for the next.
  */
 int fd_create(const fd_config* cfg, fd_handle_t* out);
 
-/* Frees the workspace and the handle.  NULL is FD_ERR_INVALID_ARG. */
+/* Frees the workspace and the handle.  NULL is FD_ERR_INVALID_ARG.  The caller makes sure no
+ * call on the handle is still running. */
 int fd_destroy(fd_handle_t h);
 
 /*
- * Re-zeroes the arrival counters on `stream` (a hipStream_t, NULL = default
- * stream).  Only needed after a call was aborted mid-kernel: every completed
- * call leaves the counters at zero by itself.
+ * Re-zeroes the arrival counters (Algorithm 4's flags) on `stream` (a hipStream_t, NULL =
+ * default stream).  Only needed after a call was aborted mid-kernel or a fd_decode_waits call
+ * gave up waiting: every completed call leaves the counters at zero by itself (see fd_create).
  */
 int fd_reset(fd_handle_t h, void* stream);
 
@@ -122,14 +130,22 @@ int fd_reset(fd_handle_t h, void* stream);
  *   k_cache  [B, Hkv, S_max, D]  bf16, device; 16-byte aligned
  *   v_cache  [B, Hkv, S_max, D]  bf16, device; 16-byte aligned
  *   seq_lens [B] int32, device; 0 <= seq_lens[b] <= S_max.  Read on the device:
- *            the host never waits for it.  Rows >= seq_lens[b] are never read.
+ *            the host never waits for it.  Rows >= seq_lens[b] never influence a result
+ *            (they may hold anything, NaN included).  With n_splits > 0 a workgroup
+ *            requests the first rows of its first split (up to 256, or 512 of an FP8
+ *            cache) before seq_lens has arrived: rows below S_max of the
+ *            [B, Hkv, S_max, D] arrays may therefore be read and dropped; nothing outside
+ *            the arrays is touched.
  *   out      [B, Hq, D] fp32, device:  softmax(scale * q K^T) V
  *   lse      [B, Hq]    fp32, device, natural log of sum_j exp(score_j);
  *            may be NULL (then it is not written)
- *   n_splits > 0: every sequence is cut into exactly n_splits contiguous key
- *                 ranges (trailing ranges may be empty); n_splits <= max_splits.
- *            = 0: adaptive, n_b = clamp(ceil(seq_lens[b]/512), 1, max_splits),
- *                 computed on the device.
+ *   n_splits > 0: the key axis [0, S_max) is cut into n_splits equal ranges of
+ *                 ceil(S_max / n_splits) keys, rounded up to 64; a sequence uses the
+ *                 ranges below seq_lens[b] (the last one cut short, the rest empty);
+ *                 n_splits <= max_splits.
+ *            = 0: adaptive, n_b = clamp(ceil(seq_lens[b]/512), 1, max_splits) ranges of
+ *                 the sequence's own length, computed on the device (FD_OPT_SPLIT_KEYS
+ *                 replaces the 512).
  *   stream   hipStream_t (NULL = default stream)
  *
  * seq_lens[b] == 0 gives out = 0 and lse = -inf for that sequence.
@@ -176,7 +192,8 @@ int fd_decode_waits(fd_handle_t h, const void* q, const void* k_cache, const voi
  *   pages_per_seq     row length of block_table; pages_per_seq * page_size >= S_max
  *   everything else   as for fd_decode (S_max of the handle bounds seq_lens[b])
  *
- * Rows of a sequence's last page at or past seq_lens[b] are never read.  The MFMA kernel
+ * Rows at or past seq_lens[b] are never read here (no early request: the page must be looked
+ * up first).  The MFMA kernel
  * serves every group size here (FD_OPT_PATH = 1 is FD_ERR_UNSUPPORTED): each wave looks up
  * the page of each of its 16-key blocks; page numbers are staged in LDS 256 blocks ahead,
  * so the streaming loop is the contiguous one plus one LDS read per block.
@@ -212,12 +229,17 @@ int fd_decode_static(const fd_config* cfg, const void* q, const void* k_cache, c
 
 /*
  * Picks the handle's options by measurement: SYNCHRONOUS, unlike every other call here.
- * Runs fd_decode on the given arguments (3 untimed + `reps` timed calls, HIP events on
- * `stream`) for every combination of FD_OPT_XCD_GROUPS {1, 8 where allowed} with
- * (FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES) in {(1,2), (1,3), (1,4), (2,2)} of the MFMA
- * kernel, plus the VALU kernel where Hq/Hkv <= 8, and leaves the handle set to the
- * fastest (read the choice back with fd_get_option); *best_us (host, may be NULL) receives
- * its mean time per call in microseconds.  out / lse hold a valid result afterwards.  On
+ * The one-GPU counterpart of the paper's joint tuning of transfer granularity and kernel tiling
+ * (Section 6.3).  Runs fd_decode on the given arguments (3 untimed + `reps` timed calls, HIP
+ * events on `stream`) for every combination of
+ *   - the split granularity FD_OPT_SPLIT_KEYS in {256, 512, 1024, 2048} when n_splits = 0
+ *     (a fixed n_splits is the caller's choice and is left alone),
+ *   - FD_OPT_XCD_GROUPS in {1, 8 where B*Hkv is a multiple of 8},
+ *   - (FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES) in {(1,2), (2,2), (1,3), (1,4)} of the MFMA kernel
+ *     (the deeper rings for bf16 only), plus the VALU kernel for bf16 with Hq/Hkv <= 8;
+ * combinations the shape does not allow are skipped.  Leaves the handle set to the fastest (read
+ * the choice back with fd_get_option); *best_us (host, may be NULL) receives its mean time per
+ * call in microseconds.  out / lse hold a result of the chosen combination afterwards.  On
  * error the options are left as they were.  The defaults are rules fitted to measurements
  * on a few shapes; this call replaces the rule by the measurement for the shape and the
  * data placement at hand (the rules miss by up to 10 % on shapes between their samples).
@@ -235,10 +257,15 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
  *                        tiles with S_max > 16384; else 1), 1 = one global item list,
  *                        8 = items of a tile stay on one XCD (tile t -> workgroups with
  *                        id % 8 == t % 8)
- *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto)
+ *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto: 1 for the MFMA
+ *                        kernel).  The MFMA kernel runs 1 or 2: a call with a larger value set
+ *                        fails with FD_ERR_INVALID_ARG
  *   FD_OPT_RING_STAGES   MFMA kernel: stages (16 keys of K and V, 8 KB) in each wave's
- *                        LDS ring: 0 auto (2), 2, 3 or 4; with 2 workgroups per CU always 2
+ *                        LDS ring: 0 auto (2), 2, 3 or 4; always 2 with 2 workgroups per CU,
+ *                        half inputs or a paged cache
  *   FD_OPT_SPIN_LIMIT    fd_decode_waits: polls before a waiting workgroup gives up (0 = 1048576, about a second)
+ *   FD_OPT_SPLIT_KEYS    n_splits = 0: keys per split the split count is derived from (0 = 512;
+ *                        else a multiple of 64 in 64..65536)
  *   FD_INFO_*            read-only, through fd_get_option; FD_INFO_WAIT_GAVE_UP synchronises the device
  */
 enum {
@@ -269,7 +296,7 @@ int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n);
  * capacity_workgroups * FD_TRACE_EVENTS uint64 in which every workgroup of later
  * fused / split launches records 100 MHz timestamps of its milestones: 0 start,
  * 1 first stage landed, 2 loop end, 3 partial stored, 4 stores acknowledged,
- * 5 counted, 6 combined, 7 end, and inside a combine 8 live list built, 9 fence
+ * 5 counted, 6 combined, 7 end, and inside a combine 8 entered, 9 fence
  * passed, 10 weights ready, 11 rows accumulated (the last key range of the
  * workgroup wins; 0 = not reached).  Launches with more workgroups than the
  * capacity record nothing.  The caller owns the buffer.

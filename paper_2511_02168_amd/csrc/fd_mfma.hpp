@@ -225,6 +225,7 @@ __device__ __forceinline__ void mfma_consume_stage(const char* stage, const bf16
 struct MfmaPrefetch {
     bf16x8_t qb[4];
     int j0;          // start of the range the stages were aimed at; -1 = nothing requested
+    int j1_max;      // no block at or past this key was requested
     __device__ __forceinline__ void reset() { j0 = -1; }
     __device__ __forceinline__ bool any() const { return j0 >= 0; }
 };
@@ -242,11 +243,11 @@ __device__ __forceinline__ void mfma_load_q(const Params& p, int b, int kvh, int
     }
 }
 
-// Requests q and each wave's first 16-key block of the range starting at j0 of tile (b, kvh),
-// knowing only that the range ends at or before j1_max <= S_max (contiguous cache).  Rows up to
-// j1_max - 1 may be read: inside the cache, possibly past the sequence's end; a block that turns
-// out not to lie wholly inside the real range is requested again by mfma_item, so what was read
-// past the end is never used.
+// Requests q and each wave's first NST - 1 16-key blocks (the stages the loop keeps in flight) of the range starting at j0
+// of tile (b, kvh), knowing only that the range ends at or before j1_max <= S_max (contiguous
+// cache).  Rows up to j1_max - 1 may be read: inside the cache, possibly past the sequence's end;
+// a block that turns out not to lie wholly inside the real range is requested again by
+// mfma_item, so what was read past the end is never used.
 template <int NST>
 __device__ __forceinline__ void mfma_prefetch(const Params& p, int b, int kvh, int j0, int j1_max, char* ring,
                                               MfmaPrefetch& pf)
@@ -255,10 +256,14 @@ __device__ __forceinline__ void mfma_prefetch(const Params& p, int b, int kvh, i
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     mfma_load_q(p, b, kvh, lane, pf.qb);
     pf.j0 = j0;
-    const int kb = j0 + wave * kMfBlockKeys;
-    if (kb < j1_max) {
-        const size_t row = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max + (size_t)kb;
-        mfma_issue_stage(lds_address(ring + wave * (NST * kMfStageBytes)), p.k + row * kD, p.v + row * kD, kb, j1_max, lane);
+    pf.j1_max = j1_max;
+    const size_t row0 = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) {
+        const int kb = j0 + (wave + kWaves * s) * kMfBlockKeys;
+        if (kb < j1_max)
+            mfma_issue_stage(lds_address(ring + (wave * NST + s) * kMfStageBytes), p.k + (row0 + kb) * kD, p.v + (row0 + kb) * kD,
+                             kb, j1_max, lane);
     }
 }
 
@@ -308,12 +313,25 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
     // aimed at this range and the block lies wholly inside it; a prefetched block that does not
     // is waited for and requested again below.
     bf16x8_t qb[4];
-    bool stage0_requested = false;
+    int n_requested = 0;                  // leading stages of this wave that are already on their way (or landed)
     if (!paged && pf.any()) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) qb[t] = pf.qb[t];
-        stage0_requested = pf.j0 == j0 && j0 + (wave + 1) * kMfBlockKeys <= j1;
-        if (!stage0_requested) wait_loads_landed();
+        // a prefetched block counts if it was aimed at this range and lies wholly inside it;
+        // if any block the prefetch requested does not, wait for all of them before the ring
+        // slots are requested again
+        int n_issued = NST - 1, n_valid = 0;
+        if (pf.j0 == j0) {
+            n_issued = 0;
+#pragma unroll
+            for (int s = 0; s < NST - 1; ++s) {
+                const int kb = j0 + (wave + kWaves * s) * kMfBlockKeys;
+                n_issued += kb < pf.j1_max;
+                n_valid += kb + kMfBlockKeys <= j1;
+            }
+        }
+        if (n_valid != n_issued) wait_loads_landed();
+        n_requested = n_valid;
         pf.reset();
     } else {
         mfma_load_q(p, b, kvh, lane, qb);
@@ -353,8 +371,9 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             }
             mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
         };
-        for (int s = 0; s < P && s < cmine; ++s)
-            if (!(stage0_requested && c0 + s == 0)) issue(s);
+        // NST - 1 stages go out up front (measured: requesting the whole ring at once and
+        // waiting for all of it starts the first consume later and loses half a microsecond)
+        for (int s = (c0 == 0 ? n_requested : 0); s < P && s < cmine; ++s) issue(s);
         // Make the compiler wait for the q loads HERE: the loop below must contain no
         // compiler-generated vmcnt wait, which would also drain the stage loads the loop
         // keeps in flight (they are issued from inline asm, invisible to its counter).
@@ -365,7 +384,8 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
         const int full = kb_last + kMfBlockKeys <= j1 ? cmine : cmine - 1;
         for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
-            // the caller's side job, once, by wave 0, with this wave's requests in flight
+            // the caller's side job, once, by wave 0, right after a request has gone out: the
+            // wave has time to spare then
             if (c0 + s == 0 && wave == 0) hook();
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);

@@ -145,7 +145,7 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
     }
 }
 
-// mfma_prefetch for an FP8 cache: q and each wave's first 32-key block.
+// mfma_prefetch for an FP8 cache: q and each wave's first NST - 1 32-key blocks.
 template <int NST>
 __device__ __forceinline__ void mfma8_prefetch(const Params& p, int b, int kvh, int j0, int j1_max, char* ring,
                                                MfmaPrefetch& pf)
@@ -154,11 +154,15 @@ __device__ __forceinline__ void mfma8_prefetch(const Params& p, int b, int kvh, 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     mfma_load_q(p, b, kvh, lane, pf.qb);
     pf.j0 = j0;
-    const int kb = j0 + wave * kM8BlockKeys;
-    if (kb < j1_max) {
-        const size_t row = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max + (size_t)kb;
-        mfma8_issue_stage(lds_address(ring + wave * (NST * kMfStageBytes)), reinterpret_cast<const uint8_t*>(p.k) + row * kM8RowBytes,
-                          reinterpret_cast<const uint8_t*>(p.v) + row * kM8RowBytes, kb, j1_max, lane);
+    pf.j1_max = j1_max;
+    const size_t row0 = ((size_t)b * p.Hkv + kvh) * (size_t)p.S_max;
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) {
+        const int kb = j0 + (wave + kWaves * s) * kM8BlockKeys;
+        if (kb < j1_max)
+            mfma8_issue_stage(lds_address(ring + (wave * NST + s) * kMfStageBytes),
+                              reinterpret_cast<const uint8_t*>(p.k) + (row0 + kb) * kM8RowBytes,
+                              reinterpret_cast<const uint8_t*>(p.v) + (row0 + kb) * kM8RowBytes, kb, j1_max, lane);
     }
 }
 
@@ -194,12 +198,25 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
 
     // q and this wave's stage 0: from the prefetch if it aimed at this range (see mfma_item)
     bf16x8_t qb[4];
-    bool stage0_requested = false;
+    int n_requested = 0;                  // leading stages of this wave that are already on their way (or landed)
     if (!PAGED && pf.any()) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) qb[t] = pf.qb[t];
-        stage0_requested = pf.j0 == j0 && j0 + (wave + 1) * kM8BlockKeys <= j1;
-        if (!stage0_requested) wait_loads_landed();
+        // a prefetched block counts if it was aimed at this range and lies wholly inside it;
+        // if any block the prefetch requested does not, wait for all of them before the ring
+        // slots are requested again
+        int n_issued = NST - 1, n_valid = 0;
+        if (pf.j0 == j0) {
+            n_issued = 0;
+#pragma unroll
+            for (int s = 0; s < NST - 1; ++s) {
+                const int kb = j0 + (wave + kWaves * s) * kM8BlockKeys;
+                n_issued += kb < pf.j1_max;
+                n_valid += kb + kM8BlockKeys <= j1;
+            }
+        }
+        if (n_valid != n_issued) wait_loads_landed();
+        n_requested = n_valid;
         pf.reset();
     } else {
         mfma_load_q(p, b, kvh, lane, qb);
@@ -231,8 +248,9 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
             }
             mfma8_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
         };
-        for (int s = 0; s < P && s < cmine; ++s)
-            if (!(stage0_requested && c0 + s == 0)) issue(s);
+        // NST - 1 stages go out up front (measured: requesting the whole ring at once and
+        // waiting for all of it starts the first consume later and loses half a microsecond)
+        for (int s = (c0 == 0 ? n_requested : 0); s < P && s < cmine; ++s) issue(s);
         // the compiler's wait for the q loads goes here, outside the loop (see mfma_item)
         asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
         // the range's last block, if ragged, after the loop (see mfma_item)
@@ -240,7 +258,8 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
         const int full = kb_last + kM8BlockKeys <= j1 ? cmine : cmine - 1;
         for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
-            // the caller's side job, once, by wave 0, with this wave's requests in flight
+            // the caller's side job, once, by wave 0, right after a request has gone out: the
+            // wave has time to spare then
             if (c0 + s == 0 && wave == 0) hook();
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);

@@ -1,5 +1,7 @@
-// Partial attention of one item on the vector ALUs (used when the GQA group
-// G = Hq/Hkv is below 8, where a matrix-core tile would be mostly padding).
+// Partial attention of one item on the vector ALUs, for GQA groups G = Hq/Hkv up to 8.
+// A second, selectable implementation (FD_OPT_PATH = 1) and a cross-check: the MFMA kernel
+// is the default at every group size, because its K/V stream needs no registers and the
+// HBM bound hides the padding of its matrix tiles.
 //
 // Steps a2-a6 of the hot path (paper Section 4.2.1: partial attention of the
 // query against a KV shard, with online-softmax statistics; Algorithm 4 Part 1).

@@ -103,3 +103,37 @@ def test_host_computed_division_constants(tmp_path):
     subprocess.run(["g++", "-O2", "-o", str(exe), src], check=True)
     res = subprocess.run([str(exe)], capture_output=True, text=True)
     assert res.returncode == 0 and res.stdout.startswith("OK"), res.stdout[-500:]
+
+
+def test_host_half_under_address_and_undefined_behaviour_sanitizers():
+    """The host half of libfd.so built with ASan + UBSan (device code untouched) and driven by
+    tests/abi_host_check.c through every refusal path of the ABI, from two threads.  No kernel is launched.
+    The sanitized library is cached in the temp directory under a hash of the sources (the device code takes
+    about a minute to compile)."""
+    import hashlib
+    import subprocess
+    import tempfile
+    csrc = os.path.join(ROOT, "paper_2511_02168_amd", "csrc")
+    files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "fd.h")]
+    digest = hashlib.sha256(b"".join(open(f, "rb").read() for f in files)).hexdigest()[:16]
+    work = os.path.join(tempfile.gettempdir(), f"fd_host_san_{digest}")
+    os.makedirs(work, exist_ok=True)
+    lib = os.path.join(work, "libfd_host_san.so")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    if not os.path.exists(lib):
+        cmd = ["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O2", "-std=c++17", "-fPIC", "-shared", *san,
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+               "-Wno-inline-asm", "-o", lib + ".tmp", os.path.join(csrc, "fd_lib.hip")]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-2000:]
+        os.replace(lib + ".tmp", lib)
+    exe = os.path.join(work, "abi_host_check")
+    cmd = ["/opt/rocm/lib/llvm/bin/clang", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-I", os.path.join(ROOT, "include"), "-o", exe, os.path.join(ROOT, "tests", "abi_host_check.c"),
+           "-L", work, "-lfd_host_san", f"-Wl,-rpath,{work}", "-lpthread"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert res.returncode == 0 and res.stdout.startswith("OK"), (res.stdout + res.stderr)[-3000:]
