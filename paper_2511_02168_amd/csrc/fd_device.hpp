@@ -24,6 +24,7 @@ constexpr int kWaves = kWgThreads / 64;
 constexpr int kSplitAlign = 64;    // split lengths are multiples of this many keys
 constexpr int kAdaptiveKeys = 512; // default keys per split when the library chooses
 constexpr int kMaxGroupTiles = 2048;  // tiles one XCD group can index in adaptive mode
+constexpr int kLseStride = 32;        // floats per slot of part_lse: one 128-byte line per slot (G <= 16 used)
 constexpr float kNegBig = -3.0e38f;   // finite stand-in for "no key seen yet"
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -39,7 +40,7 @@ struct Params {
     float* out;               // [B, Hq, D]
     float* lse;               // [B, Hq] or null
     float* part_o;            // [B*Hkv, max_splits, G, D]
-    float* part_lse;          // [B*Hkv, max_splits, G]   (log2 units)
+    float* part_lse;          // [B*Hkv, max_splits, kLseStride], heads 0..G-1 used (log2 units)
     uint32_t* counters;       // [B*Hkv]
     uint32_t* status;         // [1] set non-zero by a waiting combine kernel that gave up
     uint32_t spin_limit;      // polls a waiting combine workgroup makes before it gives up
@@ -242,16 +243,24 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
 // ---- exchange of partials between workgroups ----------------------------------
-// A gfx950 device has 8 XCDs, each with its own L2 that is not kept coherent
-// with the others.  An agent-scope release FENCE writes back a whole L2, far too
-// heavy to run once per item.  A workgroup therefore WRITES its partial with
-// agent-scope stores (sc1: written through to the device-coherent level) and keeps
-// the order "partial, then counter" by waiting for the stores' acknowledgements
-// (s_waitcnt vmcnt(0)) before the workgroup barrier that precedes the counter
-// increment.  The one workgroup that READS a tile's partials does so after seeing the
-// complete count: first head 0's lse per slot with agent-scope loads where it scans for
-// live slots, then one acquire fence (invalidate only: nothing to write back) and
-// ordinary loads for the rows.  No other data travels between workgroups in a launch.
+// A gfx950 device has 8 XCDs, each with its own L2 that is not kept coherent with the
+// others.  An agent-scope release FENCE writes back a whole L2, far too heavy to run once
+// per item.  A workgroup therefore WRITES its partial with agent-scope stores (sc1: written
+// through to the device-coherent level) and keeps the order "partial, then counter" by
+// waiting for the stores' acknowledgements (s_waitcnt vmcnt(0)) before the workgroup
+// barrier that precedes the counter increment.
+// The one workgroup that READS a tile's partials does so after it has seen the complete count,
+// with ordinary loads and WITHOUT an acquire fence (an L2 invalidate costs 0.5-0.8 us on the
+// critical tail of every call).  That is safe because no cache on the reader's side can hold
+// a stale copy of what it reads:
+//   * every slot owns whole 128-byte lines (a partial's o block is G x 512 bytes, its lse one
+//     padded line of kLseStride floats), so no line is shared between two writers and a
+//     local writer never pulls a neighbour's not-yet-written data into the local L2;
+//   * a line of the partial buffer is read by nobody but its tile's combiner, once per
+//     launch, after the last arrival: nothing can have fetched it earlier in this launch;
+//   * what an earlier launch left in L1 / L2 is dropped at the launch boundary, as for any
+//     kernel that reads what the previous kernel wrote from another XCD.
+// No other data travels between workgroups in a launch.
 __device__ __forceinline__ void store_agent(float* p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -417,14 +426,14 @@ __device__ inline void combine_tile_unstaged(const float* plse, const float* po,
         const int g = pair / (kD / 4), d4 = pair % (kD / 4);
         float M = -INFINITY, L = 0.f;
 #pragma nounroll
-        for (int k = 0; k < n_live; ++k) M = fmaxf(M, plse[slot(k) * G + g]);
+        for (int k = 0; k < n_live; ++k) M = fmaxf(M, plse[slot(k) * kLseStride + g]);
 #pragma nounroll
-        for (int k = 0; k < n_live; ++k) L += fast_exp2(plse[slot(k) * G + g] - M);
+        for (int k = 0; k < n_live; ++k) L += fast_exp2(plse[slot(k) * kLseStride + g] - M);
         const float invL = __builtin_amdgcn_rcpf(L);
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma nounroll
         for (int k = 0; k < n_live; ++k) {
-            const float w = fast_exp2(plse[slot(k) * G + g] - M);
+            const float w = fast_exp2(plse[slot(k) * kLseStride + g] - M);
             const float4 x = po4[(size_t)(slot(k) * G + g) * (kD / 4) + d4];
             o.x += w * x.x; o.y += w * x.y; o.z += w * x.z; o.w += w * x.w;
         }
@@ -442,11 +451,11 @@ __device__ inline void combine_tile_unstaged(const float* plse, const float* po,
 // one wave per SIMD.  Two things cost time there: dependent memory round trips (0.4-1 us
 // each while the rest of the chip is still streaming) and instructions (a lone wave
 // retires only ~250 of them per microsecond).  Hence:
-//   1. wave 0 reads head 0's lse of every slot, up to 4 slots per lane in flight, and
-//      lists the live ones in ascending order (coherent loads: nothing is invalidated yet);
-//   2. acquire fence: from here on ordinary loads see the partials (they were written
-//      through to memory; the fence drops stale lines from this CU's L1 and this XCD's L2).
-//      Ordinary loads pull rows ~1.7x faster than coherent ones;
+//   1. the list of live slots is there already (fused kernel: derived from the schedule
+//      while the K/V stream ran) or wave 0 reads head 0's lse of every slot, up to 4 slots
+//      per lane in flight, and lists the live ones in ascending order;
+//   2. no acquire fence (see "exchange of partials" above): ordinary loads, which pull rows
+//      ~1.7x faster than coherent ones;
 //   3. one round trip: each thread requests its first BATCH rows of o; meanwhile 16 lanes
 //      per head fetch that head's lse values, reduce max and sum with DPP, and leave the
 //      rows' weights in LDS (zero in the padding, so the row loop needs no bounds logic);
@@ -524,7 +533,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63;
-    const float* plse = p.part_lse + (size_t)tile * p.max_splits * G;
+    const float* plse = p.part_lse + (size_t)tile * p.max_splits * kLseStride;
     const float* po = p.part_o + (size_t)tile * p.max_splits * G * kD;
     float* out_rows = p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD;
     float* lse_rows = p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr;
@@ -543,7 +552,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
             for (int j = 0; j < 4; ++j) {
                 const int i = base + j * 64 + lane;
                 first[j] = -INFINITY;
-                if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * G]);
+                if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * kLseStride]);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -560,7 +569,6 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
         combine_live_finish(ll, count, live0, log_r, lane);
     }
     trace_event(p, kEvCombA);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     __syncthreads();
     const int n_live = ll.n_live;
     trace_event(p, kEvCombB);
@@ -595,7 +603,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     for (int i = 0; i < 4; ++i) {
         const int k = sj + 16 * i;
         v[i] = -INFINITY;
-        if (stat_lane && k < n_live) v[i] = plse[live_at(k) * G + sg];
+        if (stat_lane && k < n_live) v[i] = plse[live_at(k) * kLseStride + sg];
     }
 
     float4 x[BATCH];
@@ -620,7 +628,7 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
         float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
 #pragma nounroll
         for (int k = sj + 64; k < n_live; k += 16) {     // rows past the first 64: rare, fetched here
-            const float t = plse[live_at(k) * G + sg];
+            const float t = plse[live_at(k) * kLseStride + sg];
             wg[at(k)] = t;
             m = fmaxf(m, t);
         }

@@ -188,14 +188,12 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             }
         };
         if (j0 < j1)
-            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * G, 1.0f, pf, list_live);
+            path.template item<true>(p, it.b, it.kvh, j0, j1, p.part_o + slot * G * kD, p.part_lse + slot * kLseStride, 1.0f, pf, list_live);
         else if (threadIdx.x < 64)
             list_live();
-        {
-            const int skip = j0 < j1 ? G : 0;
-            for (int i = skip + threadIdx.x; i < run * G; i += kWgThreads)
-                store_agent(&p.part_lse[slot * G + i], -INFINITY);
-        }
+        // (head 0's lse is what a combine that scans memory for live slots looks at)
+        for (int r = (j0 < j1 ? 1 : 0) + threadIdx.x; r < run; r += kWgThreads)
+            store_agent(&p.part_lse[(slot + r) * kLseStride], -INFINITY);
 
         trace_event(p, kEvPartialOut);
         if (MODE != kModeBsp) {
@@ -450,7 +448,7 @@ Layout make_layout(const fd_config& c)
     Layout l;
     l.part_o_off = 0;
     l.part_lse_off = up(tiles * c.max_splits * G * fd::kD * sizeof(float));
-    l.counters_off = l.part_lse_off + up(tiles * c.max_splits * G * sizeof(float));
+    l.counters_off = l.part_lse_off + up(tiles * c.max_splits * fd::kLseStride * sizeof(float));
     l.status_off = l.counters_off + up(tiles * sizeof(uint32_t));
     l.total = l.status_off + 256;
     return l;

@@ -9,7 +9,13 @@
 // 16-key stage, so ring, DMA count per stage and wait counts are shared with it).
 //   * QK^T: two 16-key blocks x 4 steps of v_mfma_f32_16x16x32_bf16; a lane reads the 8
 //     bytes (8 dims) of its key with one ds_read_b64.
-//   * PV: v_mfma_f32_16x16x32_bf16 with K = 32 keys.  The B operand (P) of lane
+//   * PV: v_mfma_f32_16x16x32_f16 with K = 32 keys: V is widened to IEEE half (every E4M3 value
+//     is a half value too) and P goes in as ONE half (11 significant bits, 2^-12 relative:
+//     an eighth of the output tolerance) instead of the bf16 kernel's hi + lo pair, which
+//     halves the PV matrix work and drops the split arithmetic; the weights carry a factor
+//     2^kM8PShift so that small ones stay clear of half's underflow, and the sum l carries it
+//     too, so it cancels in o = acc / l and moves into the reference maximum for the lse.
+//     The B operand (P) of lane
 //     (head, kg) is exactly the 8 scores that lane holds after QK^T (keys 4kg..4kg+3 of
 //     both blocks), so P still never moves between lanes; the A operand (V^T: 8 keys
 //     of one dim per lane) comes from ds_read_b64_tr_b8, whose 16-lane groups each
@@ -51,6 +57,24 @@ __device__ __forceinline__ bf16x8_t fp8x8_to_bf16(i32x2_t w)
     r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
     return r;
 }
+
+// 8 E4M3 bytes -> 8 IEEE halves, exactly (v_cvt_scalef32_pk_f16_fp8 with scale 1)
+__device__ __forceinline__ f16x8_t fp8x8_to_f16(i32x2_t w)
+{
+    typedef _Float16 f16x2_v __attribute__((ext_vector_type(2)));
+    const f16x2_v a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, 1.0f, false);
+    const f16x2_v b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, 1.0f, true);
+    const f16x2_v c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, 1.0f, false);
+    const f16x2_v d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, 1.0f, true);
+    f16x8_t r;
+    r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+    r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+    return r;
+}
+
+// Weights are computed as 2^(score - reference + kM8PShift): at most 2^(kRescaleSlack + kM8PShift)
+// = 2^14, far below half's largest value, and a weight 2^-32 of the largest still is a half.
+constexpr float kM8PShift = 8.0f;
 
 // Requests the 32 keys [kb, kb+32) of K and V (rows of 128 bytes starting at kp / vp,
 // wave-uniform) into one stage: 4 + 4 transfers of 8 rows.  Rows at or past j1 re-read
@@ -110,7 +134,7 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
         }
     float tm = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
     tm = head_lanes_max(tm);
-    // lazy reference maximum and hi + lo split as in mfma_consume_stage
+    // lazy reference maximum as in mfma_consume_stage
     if (__any(tm > st.m + kRescaleSlack)) {
         const float mnew = fmaxf(st.m, tm);
         const float alpha = fast_exp2(st.m - mnew);
@@ -119,15 +143,13 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
 #pragma unroll
         for (int db = 0; db < 8; ++db) st.acc[db] *= alpha;
     }
-    s16x8_t phi, plo;
+    f16x8_t ph;
+    const float mref = st.m - kM8PShift;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(p[e] - st.m);
+        p[e] = fast_exp2(p[e] - mref);
         st.l += p[e];
-        const uint32_t bits = __builtin_bit_cast(uint32_t, p[e]);
-        const __bf16 lo = (__bf16)(p[e] - __builtin_bit_cast(float, bits & 0xffff0000u));
-        phi[e] = (short)(bits >> 16);
-        plo[e] = __builtin_bit_cast(short, lo);
+        ph[e] = (_Float16)p[e];
     }
 
     // a5: O^T[dim][head] += V^T . P^T over the 32 keys, 16 dims at a time
@@ -139,9 +161,7 @@ __device__ __forceinline__ void mfma8_consume_stage(const char* stage, const bf1
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
         const i32x2_t w = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_ptr)(vrowp + ((db ^ vsw) << 4)));
-        const bf16x8_t vt = fp8x8_to_bf16(w);
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, __builtin_bit_cast(bf16x8_t, phi), st.acc[db], 0, 0, 0);
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, __builtin_bit_cast(bf16x8_t, plo), st.acc[db], 0, 0, 0);
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fp8x8_to_f16(w), ph, st.acc[db], 0, 0, 0);
     }
 }
 
@@ -276,6 +296,7 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
 
     trace_event(p, kEvLoopEnd);
     st.l = head_lanes_sum(st.l);
+    st.m -= kM8PShift;                                    // l and acc carry 2^kM8PShift: lse = (m - shift) + log2(l)
     __syncthreads();                                      // all waves are done reading their rings
     ItemSmem<kMfRows>& sm = *reinterpret_cast<ItemSmem<kMfRows>*>(ring);
     if (head < G) {

@@ -43,10 +43,10 @@ int main(void)
     CHECK(fd_version() == FD_VERSION);
     CHECK(strcmp(fd_last_error(), "") == 0);
 
-    /* workspace formula: partials, their LSEs, counters and status word, each rounded up to 256 bytes */
+    /* workspace formula: partials, one 128-byte line of LSEs per slot, counters and status word, each rounded up to 256 bytes */
     fd_config c = good();
     const size_t tiles = 4, G = 4, n = 16;
-    CHECK(fd_workspace_bytes(&c) == tiles * n * G * 128 * 4 + tiles * n * G * 4 + 256 + 256);
+    CHECK(fd_workspace_bytes(&c) == tiles * n * G * 128 * 4 + tiles * n * 128 + 256 + 256);
     CHECK(fd_workspace_bytes(NULL) == 0);
 
     /* configurations that must be refused, by fd_workspace_bytes, fd_create and fd_decode_static alike */

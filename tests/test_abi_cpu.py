@@ -41,7 +41,7 @@ def good_cfg(**kw):
 def test_workspace_bytes_formula():
     cfg = good_cfg()
     tiles, G, n = 4, 4, 16
-    expect = tiles * n * G * 128 * 4 + tiles * n * G * 4 + 256 + 256   # partials, their LSEs, counters, status word (256-byte rounded)
+    expect = tiles * n * G * 128 * 4 + tiles * n * 128 + 256 + 256   # partials, one 128-byte line of LSEs per slot, counters, status word (256-byte rounded)
     assert fd.fd_workspace_bytes(cfg) == expect
     assert fd.fd_workspace_bytes(good_cfg(D=64)) == 0
 

@@ -365,6 +365,37 @@ def test_repeat_determinism_with_poisoned_workspace():
         assert all(c == 0 for c in fd.fd_debug_read_counters(dec.h, wl.B * wl.Hkv))
 
 
+@pytest.mark.parametrize("xcd", [1, 8])
+def test_alternating_inputs_never_see_the_previous_calls_partials(xcd):
+    """Two different K/V caches attended in turn on one handle, 600 calls, the partial buffer poisoned with NaN
+    before each: every result must equal, bit for bit, the first result for the same cache.  A combine that read
+    a partial the previous call (other cache) left in some cache level, instead of what this call wrote, would
+    show.  With one work list a tile's partials come from all 8 XCDs; with eight from the combiner's own."""
+    wl = fi.workload("c2")
+    say(f"case alternating inputs, c2 with S reduced to 4096, xcd_groups={xcd}")
+    inp_a = fi.make_inputs(wl, "cuda", S_max=4096)
+    inp_b = fi.make_inputs(dataclasses.replace(wl, index=77), "cuda", S_max=4096)
+    ref_o, ref_l = oracle.decode(fi.bits(inp_b.q), fi.bits(inp_b.k), fi.bits(inp_b.v), inp_b.seq_lens.cpu().numpy())
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, 4096, max_splits=16) as dec:
+        fd.fd_set_option(dec.h, fd.FD_OPT_XCD_GROUPS, xcd)
+        first = {}
+        for name, inp in (("a", inp_a), ("b", inp_b)):
+            o, l = dec.decode(inp.q, inp.k, inp.v, inp.seq_lens, 16)
+            first[name] = (o.clone(), l.clone())
+        assert not torch.equal(first["a"][0], first["b"][0])
+        check_out(first["b"][0].cpu().numpy(), ref_o, "alternating b")
+        check_lse(first["b"][1].cpu().numpy(), ref_l, "alternating b")
+        stream = torch.cuda.current_stream().cuda_stream
+        for it in range(600):
+            name, inp = (("a", inp_a), ("b", inp_b))[it & 1]
+            fd.fd_debug_poison_workspace(dec.h, stream)
+            fn = dec.decode
+            o, l = fn(inp.q, inp.k, inp.v, inp.seq_lens, 16, bsp=(it % 5 == 4))
+            assert torch.equal(o.view(torch.int32), first[name][0].view(torch.int32)), f"iteration {it}: output differs"
+            assert torch.equal(l.view(torch.int32), first[name][1].view(torch.int32)), f"iteration {it}: lse differs"
+        assert all(c == 0 for c in fd.fd_debug_read_counters(dec.h, wl.B * wl.Hkv))
+
+
 def test_xcd_grouping_and_grid_size_change_only_rounding():
     """The launch shape decides which consecutive splits one workgroup attends in one go,
     i.e. the summation order: results may differ by rounding only, and fused == BSP
