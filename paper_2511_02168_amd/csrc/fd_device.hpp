@@ -519,6 +519,163 @@ __device__ inline void combine_live_from_schedule(LiveList& sm, const TileSchedu
     combine_live_finish(sm, count, live0, log_r, lane);
 }
 
+struct CombineArgs {
+    const float* plse;      // the tile's lse lines
+    const float* po;        // the tile's o blocks
+    float* out_rows;
+    float* lse_rows;        // or null
+    int G, n_live, KJ, log_r, stride;
+};
+
+// Second half of combine_tile: weights, row loop, output.  NG0 = row groups (of kCombineGroup
+// rows) in a thread's first batch = min(BATCH, KJ) / kCombineGroup, a template parameter so that
+// every thread issues exactly 4 lse loads and then exactly NG0 * kCombineGroup row loads,
+// unconditionally: the compiler can then wait for the lse values alone (vmcnt = the number of
+// younger row loads) and the weights are computed while the rows are still arriving.  Threads
+// with no (head, dims) pair of their own load the rows of pair 0 and drop them.
+template <int BATCH, int NG0>
+__device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs& a, CombineSmem& sm, const LiveList& ll, int tid)
+{
+    static_assert(NG0 >= 1 && NG0 * kCombineGroup <= BATCH, "first batch");
+    const int G = a.G, n_live = a.n_live, KJ = a.KJ, log_r = a.log_r, stride = a.stride;
+    const int R = 1 << log_r;
+    const int kPairs = G * (kD / 4);
+    // thread -> (pair, slice) without an integer division
+    const int slice = (int)(((tid >> 5) + 0.5f) * __builtin_amdgcn_rcpf((float)G));
+    const int pair0 = tid - slice * kPairs;
+    const size_t row_f4 = (size_t)G * (kD / 4);          // float4 per slot
+    const float4* po4 = reinterpret_cast<const float4*>(a.po);
+    const bool active0 = slice < R && pair0 < kPairs;
+    const int* my_live = &ll.live[(active0 ? slice : 0) * stride];
+
+    // weights: 16 lanes per head, lane j takes rows j, j+16, ...; the lse loads go out first
+    const bool stat_lane = (tid >> 4) < G;
+    const int sg = stat_lane ? tid >> 4 : 0, sj = tid & 15;
+    const auto live_at = [&](int k) { return ll.live[(k & (R - 1)) * stride + (k >> log_r)]; };
+    if (n_live > 64 && stat_lane) {                      // rows past the first 64: rare, staged through LDS
+        float* wg = &sm.w[sg * R * KJ];
+#pragma nounroll
+        for (int k = sj + 64; k < n_live; k += 16) wg[(k & (R - 1)) * KJ + (k >> log_r)] = a.plse[live_at(k) * kLseStride + sg];
+    }
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = sj + 16 * i;
+        v[i] = a.plse[live_at(k < n_live ? k : 0) * kLseStride + sg];
+    }
+
+    float4 x[BATCH];
+    {
+        const int pair = active0 ? pair0 : 0;
+#pragma unroll
+        for (int j = 0; j < NG0 * kCombineGroup; ++j) x[j] = po4[my_live[j] * row_f4 + pair];
+    }
+    const auto load_rows = [&](int j0, int pair) {       // groups of rows [j0, j0 + BATCH) below KJ
+#pragma unroll
+        for (int grp = 0; grp < BATCH / kCombineGroup; ++grp) {
+            if (j0 + grp * kCombineGroup < KJ) {
+#pragma unroll
+                for (int u = 0; u < kCombineGroup; ++u) {
+                    const int j = grp * kCombineGroup + u;
+                    x[j] = po4[my_live[j0 + j] * row_f4 + pair];
+                }
+            }
+        }
+    };
+
+    if (stat_lane) {
+        float* wg = &sm.w[sg * R * KJ];
+        const auto at = [&](int k) { return (k & (R - 1)) * KJ + (k >> log_r); };
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (sj + 16 * i >= n_live) v[i] = -INFINITY;
+        float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+#pragma nounroll
+        for (int k = sj + 64; k < n_live; k += 16) m = fmaxf(m, wg[at(k)]);
+        const float M = row16_max(m);
+        float l = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = sj + 16 * i;
+            if (k < R * KJ) {
+                const float e = fast_exp2(v[i] - M);     // 0 for the padding (v = -inf)
+                wg[at(k)] = e;
+                l += e;
+            }
+        }
+#pragma nounroll
+        for (int k = sj + 64; k < R * KJ; k += 16) {
+            const float e = k < n_live ? fast_exp2(wg[at(k)] - M) : 0.f;
+            wg[at(k)] = e;
+            l += e;
+        }
+        const float L = row16_sum(l);
+        if (sj == 0) {
+            sm.invL[sg] = __builtin_amdgcn_rcpf(L);
+            if (a.lse_rows) a.lse_rows[sg] = (M + fast_log2(L)) * kLn2;
+        }
+    }
+    __syncthreads();
+    trace_event(p, kEvCombC);
+
+#pragma nounroll
+    for (int pbase = 0; pbase < kPairs; pbase += kWgThreads) {
+        const int pair = pbase + pair0;
+        const bool active = slice < R && pair < kPairs;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (active) {
+            const int g = pair >> 5;
+            const float* my_w = &sm.w[(g * R + slice) * KJ];
+            if (pbase > 0) load_rows(0, pair);
+            // first batch: NG0 groups, known to lie below KJ
+#pragma unroll
+            for (int j = 0; j < NG0 * kCombineGroup; ++j) {
+                const float w = my_w[j];
+                o.x += w * x[j].x;
+                o.y += w * x[j].y;
+                o.z += w * x[j].z;
+                o.w += w * x[j].w;
+            }
+            // further batches (more than BATCH rows per slice: rare)
+#pragma nounroll
+            for (int j0 = BATCH; j0 < KJ; j0 += BATCH) {
+                load_rows(j0, pair);
+#pragma unroll
+                for (int grp = 0; grp < BATCH / kCombineGroup; ++grp) {
+                    if (j0 + grp * kCombineGroup < KJ) {
+#pragma unroll
+                        for (int u = 0; u < kCombineGroup; ++u) {
+                            const int j = grp * kCombineGroup + u;
+                            const float w = my_w[j0 + j];
+                            o.x += w * x[j].x;
+                            o.y += w * x[j].y;
+                            o.z += w * x[j].z;
+                            o.w += w * x[j].w;
+                        }
+                    }
+                }
+            }
+            const float invL = sm.invL[g];
+            o.x *= invL; o.y *= invL; o.z *= invL; o.w *= invL;
+        }
+        trace_event(p, kEvCombD);
+        if (R > 1) {
+            sm.red[tid] = o;
+            __syncthreads();
+            if (active && slice == 0) {
+#pragma nounroll
+                for (int r = 1; r < R; ++r) {
+                    const float4 t = sm.red[r * kPairs + pair];
+                    o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+                }
+                reinterpret_cast<float4*>(a.out_rows)[pair] = o;
+            }
+        } else if (active) {
+            reinterpret_cast<float4*>(a.out_rows)[pair] = o;
+        }
+    }
+}
+
 // live_ready: the live list is already in sm (combine_live_from_schedule); otherwise wave 0
 // finds the live slots by reading head 0's lse of every slot.
 template <int BATCH>
@@ -538,7 +695,6 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     float* out_rows = p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD;
     float* lse_rows = p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr;
 
-    const int kPairs = G * (kD / 4);
     const int log_r = combine_log_r(G);
     const int R = 1 << log_r;
     const int stride = combine_live_stride(log_r);       // of one slice's live list
@@ -551,8 +707,8 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = base + j * 64 + lane;
-                first[j] = -INFINITY;
-                if (base + j * 64 < n && i < n) first[j] = load_agent(&plse[i * kLseStride]);
+                first[j] = load_agent(&plse[min(i, n - 1) * kLseStride]);     // unconditional: the 4 loads fly together
+                if (i >= n) first[j] = -INFINITY;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -586,126 +742,14 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
         return;
     }
 
-    // thread -> (pair, slice) without an integer division
-    const int slice = (int)(((tid >> 5) + 0.5f) * __builtin_amdgcn_rcpf((float)G));
-    const int pair0 = tid - slice * kPairs;
-    const size_t row_f4 = (size_t)G * (kD / 4);          // float4 per slot
-    const float4* po4 = reinterpret_cast<const float4*>(po);
-    const int* my_live = &ll.live[slice * stride];
-
-    // weights: 16 lanes per head, lane j takes rows j, j+16, ...  The lse loads of the first
-    // 64 rows go out BEFORE the row loads, so that the weights do not wait for the rows.
-    const bool stat_lane = (tid >> 4) < G;
-    const int sg = tid >> 4, sj = tid & 15;
-    const auto live_at = [&](int k) { return ll.live[(k & (R - 1)) * stride + (k >> log_r)]; };
-    float v[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int k = sj + 16 * i;
-        v[i] = -INFINITY;
-        if (stat_lane && k < n_live) v[i] = plse[live_at(k) * kLseStride + sg];
-    }
-
-    float4 x[BATCH];
-    const auto load_rows = [&](int j0, int pair) {       // groups of rows [j0, j0 + BATCH) below KJ
-#pragma unroll
-        for (int grp = 0; grp < BATCH / kCombineGroup; ++grp) {
-            if (j0 + grp * kCombineGroup < KJ) {
-#pragma unroll
-                for (int u = 0; u < kCombineGroup; ++u) {
-                    const int j = grp * kCombineGroup + u;
-                    x[j] = po4[my_live[j0 + j] * row_f4 + pair];
-                }
-            }
-        }
-    };
-    const bool active0 = slice < R && pair0 < kPairs;
-    if (active0) load_rows(0, pair0);
-
-    if (stat_lane) {
-        float* wg = &sm.w[sg * R * KJ];
-        const auto at = [&](int k) { return (k & (R - 1)) * KJ + (k >> log_r); };
-        float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-#pragma nounroll
-        for (int k = sj + 64; k < n_live; k += 16) {     // rows past the first 64: rare, fetched here
-            const float t = plse[live_at(k) * kLseStride + sg];
-            wg[at(k)] = t;
-            m = fmaxf(m, t);
-        }
-        const float M = row16_max(m);
-        float l = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int k = sj + 16 * i;
-            if (k < R * KJ) {
-                const float e = fast_exp2(v[i] - M);     // 0 for the padding (v = -inf)
-                wg[at(k)] = e;
-                l += e;
-            }
-        }
-#pragma nounroll
-        for (int k = sj + 64; k < R * KJ; k += 16) {
-            const float e = k < n_live ? fast_exp2(wg[at(k)] - M) : 0.f;
-            wg[at(k)] = e;
-            l += e;
-        }
-        const float L = row16_sum(l);
-        if (sj == 0) {
-            sm.invL[sg] = __builtin_amdgcn_rcpf(L);
-            if (lse_rows) lse_rows[sg] = (M + fast_log2(L)) * kLn2;
-        }
-    }
-    __syncthreads();
-    trace_event(p, kEvCombC);
-
-#pragma nounroll
-    for (int pbase = 0; pbase < kPairs; pbase += kWgThreads) {
-        const int pair = pbase + pair0;
-        const bool active = slice < R && pair < kPairs;
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (active) {
-            const int g = pair >> 5;
-            const float* my_w = &sm.w[(g * R + slice) * KJ];
-            if (pbase > 0) load_rows(0, pair);
-            int j0 = 0;
-#pragma nounroll
-            while (true) {
-#pragma unroll
-                for (int grp = 0; grp < BATCH / kCombineGroup; ++grp) {
-                    if (j0 + grp * kCombineGroup < KJ) {
-#pragma unroll
-                        for (int u = 0; u < kCombineGroup; ++u) {
-                            const int j = grp * kCombineGroup + u;
-                            const float w = my_w[j0 + j];
-                            o.x += w * x[j].x;
-                            o.y += w * x[j].y;
-                            o.z += w * x[j].z;
-                            o.w += w * x[j].w;
-                        }
-                    }
-                }
-                j0 += BATCH;
-                if (j0 >= KJ) break;
-                load_rows(j0, pair);
-            }
-            const float invL = sm.invL[g];
-            o.x *= invL; o.y *= invL; o.z *= invL; o.w *= invL;
-        }
-        trace_event(p, kEvCombD);
-        if (R > 1) {
-            sm.red[tid] = o;
-            __syncthreads();
-            if (active && slice == 0) {
-#pragma nounroll
-                for (int r = 1; r < R; ++r) {
-                    const float4 t = sm.red[r * kPairs + pair];
-                    o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
-                }
-                reinterpret_cast<float4*>(out_rows)[pair] = o;
-            }
-        } else if (active) {
-            reinterpret_cast<float4*>(out_rows)[pair] = o;
-        }
+    // the rest is compiled once per number of row groups in a thread's first batch, so that the
+    // number of row loads between the lse loads and their first use is a compile-time constant
+    const CombineArgs a = {plse, po, out_rows, lse_rows, G, n_live, KJ, log_r, stride};
+    switch (min(BATCH, KJ) / kCombineGroup) {
+        case 1: combine_rows<BATCH, 1>(p, a, sm, ll, tid); break;
+        case 2: combine_rows<BATCH, (BATCH >= 16 ? 2 : 1)>(p, a, sm, ll, tid); break;
+        case 3: combine_rows<BATCH, (BATCH >= 24 ? 3 : 1)>(p, a, sm, ll, tid); break;
+        default: combine_rows<BATCH, (BATCH >= 32 ? 4 : 1)>(p, a, sm, ll, tid); break;
     }
     __syncthreads();
 }
