@@ -56,8 +56,21 @@ def parse_args():
     return ap.parse_args()
 
 
+def settle(fn, torch, seconds=0.12):
+    """Untimed calls until the device has been busy for a while: the first tens of milliseconds of work after an
+    idle period run measurably slower (1-3 %), whatever kernel is launched; no timed loop starts inside them."""
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(50):
+            fn(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
 def time_calls(fn, n_warm, n_steps, torch):
     """Mean duration of one call in ms: HIP events on the launch stream around n_steps calls."""
+    settle(fn, torch)
     for i in range(n_warm):
         fn(i)
     torch.cuda.synchronize()
