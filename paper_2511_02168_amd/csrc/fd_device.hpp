@@ -28,28 +28,18 @@ constexpr int kLseStride = 32;        // floats per slot of part_lse: one 128-by
 constexpr float kNegBig = -3.0e38f;   // finite stand-in for "no key seen yet"
 constexpr float kLn2 = 0.6931471805599453f;
 
+// Kernel arguments.  The fields a workgroup needs before its first K/V request come first, within
+// the first two 64-byte lines of the argument block, so that they arrive with the first scalar loads.
 struct Params {
-    const uint16_t* q;        // [B, Hq, D] bf16
     const uint16_t* k;        // [B, Hkv, S_max, D] bf16, or the page pool [num_pages, Hkv, page_size, D]
     const uint16_t* v;        // like k
-    const int32_t* block_table;  // paged cache: [B, pages_per_seq], pool page of each logical page; null = contiguous
-    int32_t page_shift;       // log2(page_size)
-    int32_t pages_per_seq;
-    int32_t num_pages;
+    const uint16_t* q;        // [B, Hq, D] bf16
     const int32_t* seq_lens;  // [B]
-    float* out;               // [B, Hq, D]
-    float* lse;               // [B, Hq] or null
-    float* part_o;            // [B*Hkv, max_splits, G, D]
-    float* part_lse;          // [B*Hkv, max_splits, kLseStride], heads 0..G-1 used (log2 units)
-    uint32_t* counters;       // [B*Hkv]
-    uint32_t* status;         // [1] set non-zero by a waiting combine kernel that gave up
-    uint32_t spin_limit;      // polls a waiting combine workgroup makes before it gives up
     int32_t B, Hq, Hkv, G, S_max;
     int32_t n_splits;         // 0 = adaptive
-    int32_t max_splits;
     int32_t xcd_groups;       // 1 or 8
     int32_t xcd_shift;        // log2(xcd_groups)
-    int32_t adaptive_keys;    // adaptive mode: keys per split the split count is derived from
+    int32_t grid;             // workgroups of the persistent launch
     // Fixed n_splits: what the host can work out before the launch, so that a workgroup reaches
     // its first K/V request after a few dozen instructions.
     int32_t split_keys;       // keys per split (from S_max, a multiple of kSplitAlign); 0 in adaptive mode
@@ -57,9 +47,22 @@ struct Params {
     int32_t sched_members, sched_base, sched_rem;
     FastDiv div_n_splits;     // division by n_splits (fixed mode)
     FastDiv div_hkv;          // division by Hkv
+    int32_t max_splits;
+    int32_t adaptive_keys;    // adaptive mode: keys per split the split count is derived from
     float scale_log2;         // softmax scale * log2(e) (FP8 cache: times k_scale)
     float out_mul;            // factor on every normalised output row: 1, or v_scale of an FP8 cache
     unsigned long long* trace;  // optional [grid][kTraceEvents] timestamps (100 MHz), or null
+    float* out;               // [B, Hq, D]
+    float* lse;               // [B, Hq] or null
+    float* part_o;            // [B*Hkv, max_splits, G, D]
+    float* part_lse;          // [B*Hkv, max_splits, kLseStride], heads 0..G-1 used (log2 units)
+    uint32_t* counters;       // [B*Hkv]
+    uint32_t* status;         // [1] set non-zero by a waiting combine kernel that gave up
+    uint32_t spin_limit;      // polls a waiting combine workgroup makes before it gives up
+    const int32_t* block_table;  // paged cache: [B, pages_per_seq], pool page of each logical page; null = contiguous
+    int32_t page_shift;       // log2(page_size)
+    int32_t pages_per_seq;
+    int32_t num_pages;
 };
 
 // ---- optional in-kernel timeline (for tuning; off unless a buffer is attached) --
@@ -69,6 +72,12 @@ enum { kEvStart = 0, kEvFirstStage = 1, kEvLoopEnd = 2, kEvPartialOut = 3, kEvSt
 __device__ __forceinline__ void trace_event(const Params& p, int ev)
 {
     if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * kTraceEvents + ev] = wall_clock64();
+}
+// the same with a time taken earlier (the kernel's entry is stamped after the prologue's requests
+// have gone out: looking at p.trace first would put a dependent branch in front of them)
+__device__ __forceinline__ void trace_event_at(const Params& p, int ev, unsigned long long t)
+{
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * kTraceEvents + ev] = t;
 }
 
 // Sequence length as the kernels use it: clamped into [0, S_max] so that a bad
@@ -135,7 +144,7 @@ __device__ inline void worklist_init(const Params& p, WorkList& wlst, int* pre, 
         wlst.last = block_first(wlst.wl + 1, wlst.base, wlst.rem);
         return;
     }
-    wlst.members = (int)(gridDim.x - wlst.x + X - 1) >> p.xcd_shift;
+    wlst.members = (p.grid - wlst.x + X - 1) >> p.xcd_shift;
     wlst.n_tiles = wlst.x < T ? (T - wlst.x + X - 1) >> p.xcd_shift : 0;
     if (p.n_splits > 0) {
         wlst.n_items = wlst.n_tiles * p.n_splits;

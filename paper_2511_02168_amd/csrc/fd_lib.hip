@@ -108,8 +108,12 @@ constexpr uint32_t kTileDirect = 0x80000000u;
 template <int MODE, int COMB_BATCH, class Path>
 __device__ __forceinline__ void persistent_loop(const Params& p, const Path& path, SchedSmem& ss, CombineSmem& comb)
 {
+    const unsigned long long t_entry = wall_clock64();
+    // Ask for every line of the argument block at once: left alone, the compiler fetches each
+    // field at its first use, three dependent scalar-cache misses in a row (0.25 us each)
+    // before the first K/V request can go out.
+    asm volatile("" ::"s"(p.trace), "s"(p.part_o), "s"(p.block_table), "s"(p.num_pages));
     const int G = p.G;
-    trace_event(p, kEvStart);
     const int lane = threadIdx.x & 63;
     const int sl_first = lane < p.B ? p.seq_lens[lane] : 0;     // in flight during the work-list arithmetic
     WorkList wl;
@@ -130,6 +134,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
         if (j0 < j1_max)
             path.prefetch(p, __builtin_amdgcn_readfirstlane(it0.b), __builtin_amdgcn_readfirstlane(it0.kvh), j0, j1_max, pf);
     }
+    trace_event_at(p, kEvStart, t_entry);
 
     while (e < wl.last) {
         // a run = the splits [split, s1) of one tile that fall into this workgroup's block
@@ -675,6 +680,7 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.max_splits = c.max_splits;
     p.xcd_groups = X;
     p.xcd_shift = X == 8 ? 3 : 0;
+    p.grid = (int32_t)grid;
     p.adaptive_keys = h->opt_split_keys > 0 ? h->opt_split_keys : fd::kAdaptiveKeys;
     p.split_keys = n_splits > 0 ? fd::split_keys_of(c.S_max, n_splits) : 0;
     p.div_n_splits = fd::make_fastdiv((uint32_t)(n_splits > 0 ? n_splits : 1));
