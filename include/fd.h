@@ -120,6 +120,8 @@ int fd_destroy(fd_handle_t h);
  * Re-zeroes the arrival counters (Algorithm 4's flags) on `stream` (a hipStream_t, NULL =
  * default stream).  Only needed after a call was aborted mid-kernel or a fd_decode_waits call
  * gave up waiting: every completed call leaves the counters at zero by itself (see fd_create).
+ * The clearing is a small kernel launch, not a memset, so the call may be recorded into a
+ * HIP graph with the rest of the stream.
  */
 int fd_reset(fd_handle_t h, void* stream);
 
@@ -149,6 +151,8 @@ int fd_reset(fd_handle_t h, void* stream);
  *   stream   hipStream_t (NULL = default stream)
  *
  * seq_lens[b] == 0 gives out = 0 and lse = -inf for that sequence.
+ * The device that is current when the handle was created must be current for every call
+ * on it (otherwise FD_ERR_INVALID_ARG, nothing is launched).
  * Accumulation is fp32; results match an fp64 evaluation of the definition to
  * about 1e-5 relative on N(0,1) data.
  */

@@ -30,11 +30,12 @@ namespace fd {
 // Kernels
 // ---------------------------------------------------------------------------
 
-// Clears n 32-bit words (the arrival counters and the status word of the static workspace).
-// A kernel, not a memset: a caller may be recording the stream into a graph.
-__global__ __launch_bounds__(kWgThreads) void fd_zero_words_kernel(uint32_t* dst, int n)
+// Sets n 32-bit words (arrival counters and status word to zero; the partial buffers to a NaN
+// pattern for the debug call).  A kernel, not a memset: a caller may be recording the stream
+// into a graph.
+__global__ __launch_bounds__(kWgThreads) void fd_fill_words_kernel(uint32_t* dst, size_t n, uint32_t value)
 {
-    for (int i = blockIdx.x * kWgThreads + threadIdx.x; i < n; i += gridDim.x * kWgThreads) dst[i] = 0u;
+    for (size_t i = (size_t)blockIdx.x * kWgThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kWgThreads) dst[i] = value;
 }
 
 // How a workgroup attends one key range: on the vector ALUs ...
@@ -474,6 +475,17 @@ int check_handle(fd_handle_t h)
     return FD_OK;
 }
 
+int launch_fill(void* dst, size_t bytes, uint32_t value, hipStream_t st)
+{
+    const size_t words = bytes / sizeof(uint32_t);
+    if (words == 0) return FD_OK;
+    const size_t wgs = (words + fd::kWgThreads - 1) / fd::kWgThreads;
+    hipLaunchKernelGGL(fd::fd_fill_words_kernel, dim3((unsigned)(wgs < 1024 ? wgs : 1024)), dim3(fd::kWgThreads), 0, st,
+                       (uint32_t*)dst, words, value);
+    FD_HIP(hipGetLastError());
+    return FD_OK;
+}
+
 int launch_combine(const fd::Params& p, hipStream_t st)
 {
     hipLaunchKernelGGL(fd::fd_combine_kernel, dim3(p.B * p.Hkv), dim3(fd::kWgThreads), 0, st, p);
@@ -590,6 +602,10 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
         return fail(FD_ERR_INVALID_ARG, "q, k_cache, v_cache and out must be 16-byte aligned");
     if (n_splits < 0 || n_splits > h->cfg.max_splits)
         return fail(FD_ERR_INVALID_ARG, "n_splits must be in 0..max_splits=%d (got %d)", h->cfg.max_splits, n_splits);
+    int cur_dev = 0;
+    FD_HIP(hipGetDevice(&cur_dev));
+    if (cur_dev != h->device)
+        return fail(FD_ERR_INVALID_ARG, "the handle belongs to device %d, the current device is %d", h->device, cur_dev);
     const fd_config& c = h->cfg;
     const int tiles = c.B * c.Hkv;
     int page_shift = 0;
@@ -862,9 +878,7 @@ int fd_reset(fd_handle_t h, void* stream)
 {
     int rc = check_handle(h);
     if (rc) return rc;
-    FD_HIP(hipMemsetAsync((char*)h->workspace + h->lay.counters_off, 0, h->lay.total - h->lay.counters_off,
-                          (hipStream_t)stream));
-    return FD_OK;
+    return launch_fill((char*)h->workspace + h->lay.counters_off, h->lay.total - h->lay.counters_off, 0u, (hipStream_t)stream);
 }
 
 int fd_decode(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
@@ -913,11 +927,8 @@ int fd_decode_static(const fd_config* cfg, const void* q, const void* k_cache, c
 
     // The workspace keeps what the last call on this GPU left (possibly of another shape, possibly
     // cut short): the counters and the status word must start at zero.
-    const int words = (int)((lay.total - lay.counters_off) / sizeof(uint32_t));
-    const int grid = words < 256 * fd::kWgThreads ? (words + fd::kWgThreads - 1) / fd::kWgThreads : 256;
-    hipLaunchKernelGGL(fd::fd_zero_words_kernel, dim3(grid), dim3(fd::kWgThreads), 0, (hipStream_t)stream,
-                       (uint32_t*)((char*)sd.ptr + lay.counters_off), words);
-    FD_HIP(hipGetLastError());
+    rc = launch_fill((char*)sd.ptr + lay.counters_off, lay.total - lay.counters_off, 0u, (hipStream_t)stream);
+    if (rc) return rc;
     return decode_common(&h, q, k_cache, v_cache, seq_lens, out, lse, n_splits, stream, fd::kModeFused);
 }
 
@@ -1084,8 +1095,7 @@ int fd_debug_poison_workspace(fd_handle_t h, void* stream)
 {
     int rc = check_handle(h);
     if (rc) return rc;
-    FD_HIP(hipMemsetAsync(h->workspace, 0xFF, h->lay.counters_off, (hipStream_t)stream));
-    return FD_OK;
+    return launch_fill(h->workspace, h->lay.counters_off, 0xFFFFFFFFu, (hipStream_t)stream);
 }
 
 int fd_debug_read_counters(fd_handle_t h, uint32_t* host_dst, int32_t n)

@@ -865,3 +865,61 @@ def test_fp8_kv_cache_paged(page_size):
         with pytest.raises(fd.FdError) as e:
             dec.decode_paged(pool16.q, pool16.k_pages, pool16.v_pages, pool16.block_table, 16, pool16.seq_lens, 1)
         assert e.value.code == fd.FD_ERR_UNSUPPORTED
+
+
+def test_calls_recorded_into_a_hip_graph_replay_like_eager_calls():
+    """fd_reset, fd_decode, fd_decode_bsp and fd_decode_static only launch kernels on the caller's
+    stream (no memset node, no allocation, no host wait), so a stream holding them can be recorded
+    into a HIP graph.  Every replay sees the CURRENT contents of q and seq_lens (both are read on the
+    device) and must equal an eager call on the same contents bit for bit; eager work and
+    synchronisations lie between the replays."""
+    wl = fi.Workload("graph", 8101, B=4, Hq=32, Hkv=8, S_max=5000, n_splits=12, ragged=True)
+    say(f"case {wl.name} B{wl.B} Hq{wl.Hq} Hkv{wl.Hkv} S{wl.S_max} n{wl.n_splits}")
+    inp = fi.make_inputs(wl, "cuda")
+    cfg = fd.fd_config(wl.B, wl.Hq, wl.Hkv, 128, wl.S_max, 16, 0, 0.0, fd.FD_DTYPE_BF16, 0.0, 0.0)
+    q = inp.q.clone()
+    sl = inp.seq_lens.clone()
+    outs = {name: torch.empty(wl.B, wl.Hq, 128, device="cuda") for name in ("fused", "bsp", "static")}
+    lses = {name: torch.empty(wl.B, wl.Hq, device="cuda") for name in outs}
+    side = torch.cuda.Stream()
+    with fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=16) as dec, \
+            fd.FlashDecode(wl.B, wl.Hq, wl.Hkv, wl.S_max, max_splits=16) as eager:
+
+        def record(st):
+            fd.fd_reset(dec.h, st)
+            fd.fd_decode(dec.h, q, inp.k, inp.v, sl, outs["fused"], lses["fused"], wl.n_splits, st)
+            fd.fd_decode_bsp(dec.h, q, inp.k, inp.v, sl, outs["bsp"], lses["bsp"], wl.n_splits, st)
+            fd.fd_decode_static(cfg, q, inp.k, inp.v, sl, outs["static"], lses["static"], wl.n_splits, st)
+
+        # once outside the capture: per-kernel and per-device set-up happens on a first call
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            record(side.cuda_stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            record(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+
+        gen = torch.Generator(device="cuda").manual_seed(8102)
+        for rep in range(4):
+            say(f"  replay {rep}")
+            q.copy_(torch.randn(q.shape, device="cuda", generator=gen).to(torch.bfloat16))
+            # new lengths within the rows that hold data (past the workload's own lengths lies NaN)
+            frac = torch.rand(sl.shape, device="cuda", generator=gen)
+            sl.copy_(torch.minimum((frac * (inp.seq_lens + 1)).to(torch.int32), inp.seq_lens).clamp_(min=1))
+            if rep == 2:
+                sl[0] = 0
+            ref_o, ref_l = eager.decode(q, inp.k, inp.v, sl, wl.n_splits)
+            for name in outs:
+                outs[name].fill_(float("nan"))
+                lses[name].fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for name in outs:
+                assert torch.equal(outs[name].view(torch.int32), ref_o.view(torch.int32)), f"replay {rep}: {name} out differs from eager"
+                assert torch.equal(lses[name].view(torch.int32), ref_l.view(torch.int32)), f"replay {rep}: {name} lse differs from eager"
+        o64, l64 = oracle.decode(fi.bits(q), fi.bits(inp.k), fi.bits(inp.v), sl.cpu().numpy())
+        check_out(outs["fused"].cpu().numpy(), o64, "graph replay")
+        check_lse(lses["fused"].cpu().numpy(), l64, "graph replay")
