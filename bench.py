@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--no-bsp", action="store_true")
     ap.add_argument("--no-waits", action="store_true", help="skip the fine-grained-waits variant (fd_decode_waits)")
     ap.add_argument("--no-hot", action="store_true", help="skip the hot-cache figure (one K/V copy) of the workloads that fit the Infinity Cache")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same calls")
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only streaming kernel (achievable bandwidth)")
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
@@ -83,6 +84,32 @@ def time_calls(fn, n_warm, n_steps, torch):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
     return e0.elapsed_time(e1) / n_steps, wall_ms
+
+
+def time_graph(fn, n_steps, torch):
+    """The same n_steps calls recorded once into a HIP graph and replayed: mean ms per call (None if the capture
+    fails).  The calls only launch kernels on the stream they are given, so they can be captured."""
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            st = torch.cuda.current_stream().cuda_stream
+            for i in range(n_steps):
+                fn(i, st)
+        torch.cuda.synchronize()
+        settle(fn, torch)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_steps
+    except Exception as exc:                          # a figure beside the headline: never fatal
+        print(f"bench: graph replay skipped ({exc})", file=sys.stderr)
+        return None
 
 
 def per_call_percentiles(fn, n_calls, torch):
@@ -204,23 +231,23 @@ def main():
         ks = [pg.k_pages] + [pg.k_pages.clone() for _ in range(copies - 1)]
         vs = [pg.v_pages] + [pg.v_pages.clone() for _ in range(copies - 1)]
 
-        def fused(i):
+        def fused(i, st=stream):
             j = i % copies
             fd.fd_decode_paged(dec.h, inp.q, ks[j], vs[j], pg.block_table, args.page_size, inp.seq_lens, out, lse,
-                               wl.n_splits, stream)
+                               wl.n_splits, st)
 
-        def bsp(i):
+        def bsp(i, st=stream):
             j = i % copies
             fd.fd_decode_paged(dec.h, inp.q, ks[j], vs[j], pg.block_table, args.page_size, inp.seq_lens, out, lse,
-                               wl.n_splits, stream, bsp=True)
+                               wl.n_splits, st, bsp=True)
     else:
-        def fused(i):
+        def fused(i, st=stream):
             j = i % copies
-            fd.fd_decode(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+            fd.fd_decode(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, st)
 
-        def bsp(i):
+        def bsp(i, st=stream):
             j = i % copies
-            fd.fd_decode_bsp(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, stream)
+            fd.fd_decode_bsp(dec.h, inp.q, ks[j], vs[j], inp.seq_lens, out, lse, wl.n_splits, st)
 
     if args.pmc_calibration:
         src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).fill_(1.0)
@@ -256,6 +283,12 @@ def main():
     hot_ms = None
     if not args.no_hot and copies > 1 and kv_bytes <= (256 << 20):
         hot_ms, _ = time_calls(lambda i: fused(0), args.warmup, args.steps, torch)
+    # the same calls launched as one HIP graph
+    graph_fused_ms = graph_bsp_ms = None
+    if not args.no_graph:
+        graph_fused_ms = time_graph(fused, args.steps, torch)
+        if not args.no_bsp and graph_fused_ms is not None:
+            graph_bsp_ms = time_graph(bsp, args.steps, torch)
     pct_fused = per_call_percentiles(fused, min(args.steps, 200), torch)
     pct_bsp = None if args.no_bsp else per_call_percentiles(bsp, min(args.steps, 200), torch)
     probe_gbs = None if args.no_probe else streaming_probe(fd, torch, stream)
@@ -285,6 +318,8 @@ def main():
         "us_per_call_bsp": None if bsp_ms is None else round(bsp_ms * 1e3, 3),
         "us_per_call_fine_grained_waits": None if waits_ms is None else round(waits_ms * 1e3, 3),
         "us_per_call_fused_hot_cache": None if hot_ms is None else round(hot_ms * 1e3, 3),
+        "us_per_call_fused_graph_replay": None if graph_fused_ms is None else round(graph_fused_ms * 1e3, 3),
+        "us_per_call_bsp_graph_replay": None if graph_bsp_ms is None else round(graph_bsp_ms * 1e3, 3),
         "fused_over_bsp": None if bsp_ms is None else round(fused_ms / bsp_ms, 4),
         "us_single_call_fused_p10_p50_p90": pct_fused,
         "us_single_call_bsp_p10_p50_p90": pct_bsp,

@@ -536,16 +536,20 @@ struct CombineArgs {
     int G, n_live, KJ, log_r, stride;
 };
 
-// Second half of combine_tile: weights, row loop, output.  NG0 = row groups (of kCombineGroup
-// rows) in a thread's first batch = min(BATCH, KJ) / kCombineGroup, a template parameter so that
-// every thread issues exactly 4 lse loads and then exactly NG0 * kCombineGroup row loads,
-// unconditionally: the compiler can then wait for the lse values alone (vmcnt = the number of
-// younger row loads) and the weights are computed while the rows are still arriving.  Threads
-// with no (head, dims) pair of their own load the rows of pair 0 and drop them.
-template <int BATCH, int NG0>
+// Second half of combine_tile: weights, row loop, output.  NR0 = rows in a thread's first batch
+// = min(BATCH, KJ), a template parameter so that every thread issues exactly NL lse loads and then
+// exactly NR0 row loads, unconditionally: the compiler can then wait for the lse values alone
+// (vmcnt = the number of younger row loads) and the weights are computed while the rows are still
+// arriving.  Every load costs the compute unit's one address unit some tens of cycles whether it
+// brings a live row or padding, so the padding is kept small (KJ = 1, 2, 4 or a multiple of 8).
+// Threads with no (head, dims) pair of their own load the rows of pair 0 and drop them.
+template <int BATCH, int NR0>
 __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs& a, CombineSmem& sm, const LiveList& ll, int tid)
 {
-    static_assert(NG0 >= 1 && NG0 * kCombineGroup <= BATCH, "first batch");
+    static_assert(NR0 >= 1 && NR0 <= BATCH, "first batch");
+    // lse loads per statistics lane (16 rows each): with at most 2 rows per slice there are at
+    // most 8 * 2 = 16 live rows
+    constexpr int NL = NR0 <= 2 ? 1 : 4;
     const int G = a.G, n_live = a.n_live, KJ = a.KJ, log_r = a.log_r, stride = a.stride;
     const int R = 1 << log_r;
     const int kPairs = G * (kD / 4);
@@ -566,9 +570,9 @@ __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs&
 #pragma nounroll
         for (int k = sj + 64; k < n_live; k += 16) wg[(k & (R - 1)) * KJ + (k >> log_r)] = a.plse[live_at(k) * kLseStride + sg];
     }
-    float v[4];
+    float v[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NL; ++i) {
         const int k = sj + 16 * i;
         v[i] = a.plse[live_at(k < n_live ? k : 0) * kLseStride + sg];
     }
@@ -577,7 +581,7 @@ __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs&
     {
         const int pair = active0 ? pair0 : 0;
 #pragma unroll
-        for (int j = 0; j < NG0 * kCombineGroup; ++j) x[j] = po4[my_live[j] * row_f4 + pair];
+        for (int j = 0; j < NR0; ++j) x[j] = po4[my_live[j] * row_f4 + pair];
     }
     const auto load_rows = [&](int j0, int pair) {       // groups of rows [j0, j0 + BATCH) below KJ
 #pragma unroll
@@ -636,9 +640,9 @@ __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs&
             const int g = pair >> 5;
             const float* my_w = &sm.w[(g * R + slice) * KJ];
             if (pbase > 0) load_rows(0, pair);
-            // first batch: NG0 groups, known to lie below KJ
+            // first batch: NR0 rows, known to lie below KJ
 #pragma unroll
-            for (int j = 0; j < NG0 * kCombineGroup; ++j) {
+            for (int j = 0; j < NR0; ++j) {
                 const float w = my_w[j];
                 o.x += w * x[j].x;
                 o.y += w * x[j].y;
@@ -688,7 +692,7 @@ __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs&
 // live_ready: the live list is already in sm (combine_live_from_schedule); otherwise wave 0
 // finds the live slots by reading head 0's lse of every slot.
 template <int BATCH>
-__device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm, LiveList& ll,
+__device__ __forceinline__ void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm, LiveList& ll,
                                     bool live_ready = false)
 {
     static_assert(BATCH % kCombineGroup == 0 && BATCH <= 32, "row batch");
@@ -743,8 +747,9 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
         __syncthreads();
         return;
     }
-    // rows per slice, padded to whole groups
-    const int KJ = (((n_live + R - 1) >> log_r) + kCombineGroup - 1) & ~(kCombineGroup - 1);
+    // rows per slice, padded to 1, 2, 4 or whole groups
+    const int per_slice = (n_live + R - 1) >> log_r;
+    const int KJ = per_slice <= 2 ? per_slice : per_slice <= 4 ? 4 : (per_slice + kCombineGroup - 1) & ~(kCombineGroup - 1);
     if (G * R * KJ > kCombineWCap) {
         combine_tile_unstaged(plse, po, out_rows, lse_rows, G, n_live, ll.live, log_r, stride);
         __syncthreads();
@@ -754,11 +759,14 @@ __device__ inline void combine_tile(const Params& p, int tile, int b, int kvh, i
     // the rest is compiled once per number of row groups in a thread's first batch, so that the
     // number of row loads between the lse loads and their first use is a compile-time constant
     const CombineArgs a = {plse, po, out_rows, lse_rows, G, n_live, KJ, log_r, stride};
-    switch (min(BATCH, KJ) / kCombineGroup) {
+    switch (min(BATCH, KJ)) {
         case 1: combine_rows<BATCH, 1>(p, a, sm, ll, tid); break;
-        case 2: combine_rows<BATCH, (BATCH >= 16 ? 2 : 1)>(p, a, sm, ll, tid); break;
-        case 3: combine_rows<BATCH, (BATCH >= 24 ? 3 : 1)>(p, a, sm, ll, tid); break;
-        default: combine_rows<BATCH, (BATCH >= 32 ? 4 : 1)>(p, a, sm, ll, tid); break;
+        case 2: combine_rows<BATCH, 2>(p, a, sm, ll, tid); break;
+        case 4: combine_rows<BATCH, 4>(p, a, sm, ll, tid); break;
+        case 8: combine_rows<BATCH, 8>(p, a, sm, ll, tid); break;
+        case 16: combine_rows<BATCH, (BATCH >= 16 ? 16 : 8)>(p, a, sm, ll, tid); break;
+        case 24: combine_rows<BATCH, (BATCH >= 24 ? 24 : 8)>(p, a, sm, ll, tid); break;
+        default: combine_rows<BATCH, (BATCH >= 32 ? 32 : 8)>(p, a, sm, ll, tid); break;
     }
     __syncthreads();
 }

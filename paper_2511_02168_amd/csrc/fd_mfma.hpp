@@ -60,13 +60,16 @@ __device__ __forceinline__ void dma_row4(uint32_t lds_addr, const void* gbase, u
                  : "memory", "m0");
 }
 
-// The same pointer, held in scalar registers (the value must already be wave-uniform).
-__device__ __forceinline__ const uint16_t* scalar_ptr(const uint16_t* p)
+// The same pointer, held in scalar registers (the value must already be wave-uniform).  Free where
+// the compiler knows the value to be uniform; where it cannot tell (a value that came through
+// LDS or a call it did not inline), this is what puts it into the scalar registers dma_row4 needs.
+template <class T>
+__device__ __forceinline__ const T* scalar_ptr(const T* p)
 {
     const uint64_t v = (uint64_t)(uintptr_t)p;
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const uint16_t*>((uintptr_t)(((uint64_t)hi << 32) | lo));
+    return reinterpret_cast<const T*>((uintptr_t)(((uint64_t)hi << 32) | lo));
 }
 
 template <int N>
@@ -116,6 +119,8 @@ __device__ __forceinline__ void mfma_issue_stage(uint32_t lds_stage, const uint1
 {
     const int rsub = lane >> 4, pos = lane & 15;
     const bool full = kb + kMfBlockKeys <= j1;
+    kp = scalar_ptr(kp);
+    vp = scalar_ptr(vp);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = 4 * i + rsub;                       // row of the block this lane fills
@@ -276,7 +281,7 @@ __device__ __forceinline__ void mfma_prefetch(const Params& p, int b, int kvh, i
 // of the caller that touches no global memory; wave 0 runs it once, right after its first
 // requests of the loop have gone out, in time the wave would spend waiting for them.
 template <int NST, bool PAGED, bool F16, bool SHARED, class Hook>
-__device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
+__device__ __forceinline__ void mfma_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
                                  float lse_mul, char* ring, MfmaPrefetch& pf, const Hook& hook)
 {
     static_assert(NST >= 2 && NST <= 8, "ring depth");
@@ -364,10 +369,6 @@ __device__ inline void mfma_item(const Params& p, int b, int kvh, int j0, int j1
             } else {
                 kp = kbase + (size_t)kb * kD;
                 vp = vbase + (size_t)kb * kD;
-            }
-            if (paged) {
-                kp = scalar_ptr(kp);
-                vp = scalar_ptr(vp);
             }
             mfma_issue_stage(my_ring_lds + (s % NST) * kMfStageBytes, kp, vp, kb, j1, lane);
         };

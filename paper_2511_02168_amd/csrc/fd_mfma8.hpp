@@ -84,6 +84,8 @@ __device__ __forceinline__ void mfma8_issue_stage(uint32_t lds_stage, const uint
 {
     const int rsub = lane >> 3, pos = lane & 7;
     const int last = j1 - 1 - kb;                         // last live row of the block (>= 0)
+    kp = scalar_ptr(kp);
+    vp = scalar_ptr(vp);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = 8 * i + rsub;
@@ -189,7 +191,7 @@ __device__ __forceinline__ void mfma8_prefetch(const Params& p, int b, int kvh, 
 // Attends keys [j0, j1) (j0 < j1) of tile (b, kvh) of an FP8 cache; contract as mfma_item,
 // PAGED as there (a 32-key block never straddles a page of 32 keys or more).
 template <int NST, bool PAGED, bool SHARED, class Hook>
-__device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
+__device__ __forceinline__ void mfma8_item(const Params& p, int b, int kvh, int j0, int j1, float* dst_o, float* dst_lse,
                                   float lse_mul, char* ring, MfmaPrefetch& pf, const Hook& hook)
 {
     const int tid = threadIdx.x;
@@ -260,8 +262,8 @@ __device__ inline void mfma8_item(const Params& p, int b, int kvh, int j0, int j
             if (PAGED) {
                 const int pg = __builtin_amdgcn_readfirstlane(my_pages[s]);
                 const size_t first_row = (((size_t)pg * p.Hkv + kvh) << p.page_shift) + (kb & ((1 << p.page_shift) - 1));
-                kp = reinterpret_cast<const uint8_t*>(scalar_ptr(reinterpret_cast<const uint16_t*>(kbase + first_row * kM8RowBytes)));
-                vp = reinterpret_cast<const uint8_t*>(scalar_ptr(reinterpret_cast<const uint16_t*>(vbase + first_row * kM8RowBytes)));
+                kp = kbase + first_row * kM8RowBytes;
+                vp = vbase + first_row * kM8RowBytes;
             } else {
                 kp = kbase + (size_t)kb * kM8RowBytes;
                 vp = vbase + (size_t)kb * kM8RowBytes;
