@@ -234,20 +234,27 @@ int fd_decode_static(const fd_config* cfg, const void* q, const void* k_cache, c
 /*
  * Picks the handle's options by measurement: SYNCHRONOUS, unlike every other call here.
  * The one-GPU counterpart of the paper's joint tuning of transfer granularity and kernel tiling
- * (Section 6.3).  Runs fd_decode on the given arguments (3 untimed + `reps` timed calls, HIP
- * events on `stream`) for every combination of
+ * (Section 6.3).  Runs fd_decode on the given arguments (after 0.1 s of untimed calls: 3 untimed +
+ * `reps` timed calls, HIP events on `stream`) for the options as they stand and for every
+ * combination of
  *   - the split granularity FD_OPT_SPLIT_KEYS in {256, 512, 1024, 2048} when n_splits = 0
  *     (a fixed n_splits is the caller's choice and is left alone),
  *   - FD_OPT_XCD_GROUPS in {1, 8 where B*Hkv is a multiple of 8},
  *   - (FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES) in {(1,2), (2,2), (1,3), (1,4)} of the MFMA kernel
  *     (the deeper rings for bf16 only), plus the VALU kernel for bf16 with Hq/Hkv <= 8;
- * combinations the shape does not allow are skipped.  Leaves the handle set to the fastest (read
- * the choice back with fd_get_option); *best_us (host, may be NULL) receives its mean time per
+ * combinations the shape does not allow are skipped.  A winner other than the options the handle
+ * came with is measured against them twice more and kept only if it is at least 0.5 % faster
+ * both times (a per cent is inside the spread of one pass).  Leaves the handle set to the choice (read
+ * it back with fd_get_option); *best_us (host, may be NULL) receives its mean time per
  * call in microseconds.  out / lse hold a result of the chosen combination afterwards.  On
  * error the options are left as they were.  The defaults are rules fitted to measurements
  * on a few shapes; this call replaces the rule by the measurement for the shape and the
  * data placement at hand (the rules miss by up to 10 % on shapes between their samples).
  * Results of later calls differ from the defaults' only in rounding (another partition).
+ * What is measured is repeated calls on the caller's buffers: a cache that fits the 256 MB
+ * Infinity Cache is then read from there, and the choice is the best for THAT (it can lose by a
+ * few per cent where every call reads another cache from HBM, as the layers of a model do: the
+ * defaults' rules were fitted to that case).
  */
 int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v_cache,
                 const int32_t* seq_lens, float* out, float* lse, int32_t n_splits, void* stream,
@@ -257,8 +264,10 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
  * Tuning / introspection knobs (per handle).  Unknown keys: FD_ERR_INVALID_ARG.
  *   FD_OPT_PATH          0 auto (the MFMA kernel), 1 VALU kernel (Hq/Hkv <= 8 only),
  *                        2 MFMA kernel
- *   FD_OPT_XCD_GROUPS    0 auto (8 when B*Hkv is a multiple of 8, except for at most 32
- *                        tiles with S_max > 16384; else 1), 1 = one global item list,
+ *   FD_OPT_XCD_GROUPS    0 auto (by measurement: 8 when B*Hkv is a multiple of 8 and, for a
+ *                        fixed split count, S_max <= 8192, or S_max <= 16384 with at least 64
+ *                        tiles; for adaptive splits unless there are at most 32 tiles with
+ *                        S_max > 16384; else 1), 1 = one global item list,
  *                        8 = items of a tile stay on one XCD (tile t -> workgroups with
  *                        id % 8 == t % 8)
  *   FD_OPT_WGS_PER_CU    persistent workgroups launched per compute unit (0 auto: 1 for the MFMA
