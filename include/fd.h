@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define FD_VERSION 140
+#define FD_VERSION 150
 
 enum {
     FD_OK = 0,
@@ -100,7 +100,9 @@ size_t fd_workspace_bytes(const fd_config* cfg);
 
 /*
  * Validates cfg, allocates the workspace on the current HIP device (partials
- * [B,Hkv,max_splits,G,D] fp32, their LSEs, one arrival counter per tile), zeroes
+ * [B,Hkv,max_splits,G,D] fp32, their LSEs, one arrival counter per tile; for the two-level
+ * merge of tiles with very many partials, FD_OPT_TREE_ROWS, a second partial buffer of
+ * ceil(max_splits/16) rows per tile and 64 group counters per tile), zeroes
  * the counters, and creates the stream and two events fd_decode_waits uses.
  * Synchronous.  *out receives the handle.
  * The workspace stands for Algorithm 4's inbox and signal flags.  The paper gives the problem
@@ -277,6 +279,13 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
  *                        LDS ring: 0 auto (2), 2, 3 or 4; always 2 with 2 workgroups per CU,
  *                        half inputs or a paged cache
  *   FD_OPT_SPIN_LIMIT    fd_decode_waits: polls before a waiting workgroup gives up (0 = 1048576, about a second)
+ *   FD_OPT_TREE_ROWS     a tile with more partials than this is merged in two levels: groups of 16
+ *                        partials by the workgroup that completes a group's arrival count, the
+ *                        groups' results by the one that completes the tile's (one compute unit
+ *                        pulling hundreds of partials would take longer than the K/V stream: one
+ *                        long sequence on one or two KV heads).  0 auto (64), else >= 2.
+ *                        fd_decode and fd_decode_bsp agree bitwise for any value; fd_decode_waits
+ *                        always merges in one level and then differs from them in rounding
  *   FD_OPT_SPLIT_KEYS    n_splits = 0: keys per split the split count is derived from (0 = 512;
  *                        else a multiple of 64 in 64..65536)
  *   FD_INFO_*            read-only, through fd_get_option; FD_INFO_WAIT_GAVE_UP synchronises the device
@@ -288,6 +297,7 @@ enum {
     FD_OPT_RING_STAGES = 4,
     FD_OPT_SPIN_LIMIT = 5,
     FD_OPT_SPLIT_KEYS = 6,
+    FD_OPT_TREE_ROWS = 7,
     FD_INFO_NUM_CUS = 100,
     FD_INFO_LAST_GRID = 101,   /* workgroups of the last fused / split launch */
     FD_INFO_LAST_PATH = 102,   /* 1 VALU, 2 MFMA */

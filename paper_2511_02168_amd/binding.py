@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfd.so")
 
 FD_OK, FD_ERR_INVALID_ARG, FD_ERR_UNSUPPORTED, FD_ERR_WORKSPACE, FD_ERR_HIP = 0, -1, -2, -3, -4
-FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES, FD_OPT_SPIN_LIMIT, FD_OPT_SPLIT_KEYS = 1, 2, 3, 4, 5, 6
+FD_OPT_PATH, FD_OPT_XCD_GROUPS, FD_OPT_WGS_PER_CU, FD_OPT_RING_STAGES, FD_OPT_SPIN_LIMIT, FD_OPT_SPLIT_KEYS, FD_OPT_TREE_ROWS = 1, 2, 3, 4, 5, 6, 7
 FD_DTYPE_BF16, FD_DTYPE_FP16, FD_DTYPE_FP8_KV = 0, 1, 2
 FD_INFO_NUM_CUS, FD_INFO_LAST_GRID, FD_INFO_LAST_PATH, FD_INFO_WAIT_GAVE_UP = 100, 101, 102, 103
 

@@ -63,6 +63,14 @@ struct Params {
     int32_t page_shift;       // log2(page_size)
     int32_t pages_per_seq;
     int32_t num_pages;
+    // two-level combine (tiles with more than tree_rows partials, see tree_arrive)
+    int32_t tree_rows;        // a tile with more live partials than this is merged in two levels; INT32_MAX = never
+    float* part2_o;           // [B*Hkv, group_cap, G, D] results of the first level
+    float* part2_lse;         // [B*Hkv, group_cap, kLseStride]
+    uint32_t* group_counters; // [B*Hkv, kMaxGroups] arrivals per first-level group
+    int32_t group_cap;        // first-level groups the workspace has room for per tile
+    uint32_t* bsp_direct;     // [B*Hkv] bulk-synchronous mode: 1 = kernel 1 wrote the tile's final result itself
+    int32_t bsp_groups;       // bulk-synchronous mode: workgroups per tile of kernel 2 (its gridDim.y)
 };
 
 // ---- optional in-kernel timeline (for tuning; off unless a buffer is attached) --
@@ -408,6 +416,9 @@ constexpr int kMaxSplits = 1024;
 
 constexpr int kCombineWCap = 4096;     // weights staged in LDS: heads x (live rows, padded)
 constexpr int kCombineGroup = 8;       // rows are loaded and padded in groups of this many
+constexpr int kTreeGroup = 16;         // two-level combine: partials merged by one first-level combine
+constexpr int kMaxGroups = 64;         // first-level groups per tile (kMaxSplits / kTreeGroup)
+constexpr int kTreeRowsDefault = 64;   // tiles with more live partials than this are merged in two levels
 
 // The slots of a tile that hold a partial, in ascending order: row k at
 // [(k % R) * stride + k / R] (R row slices, see combine_tile).  Kept apart from the combine's
@@ -415,6 +426,7 @@ constexpr int kCombineGroup = 8;       // rows are loaded and padded in groups o
 struct LiveList {
     int live[kMaxSplits + 8 * 32];
     int n_live;
+    int my_rank;        // position of this workgroup's own partial in the list (combine_live_from_schedule), -1 if it has none
 };
 
 struct CombineSmem {
@@ -500,11 +512,12 @@ __device__ __forceinline__ void combine_live_finish(LiveList& sm, int count, int
 // The live slots of a tile of the fused kernel follow from the schedule: no memory access.
 // Wave 0 only (all 64 lanes).  It depends on nothing another workgroup does, so the fused kernel
 // runs it early, while the wave would otherwise wait for K/V data in flight.
-__device__ inline void combine_live_from_schedule(LiveList& sm, const TileSchedule& sch, int n, int G)
+__device__ inline void combine_live_from_schedule(LiveList& sm, const TileSchedule& sch, int n, int G, int my_block)
 {
     const int lane = threadIdx.x & 63;
     const int log_r = combine_log_r(G), R = 1 << log_r, stride = combine_live_stride(log_r);
     int count = 0, live0 = 0;
+    if (lane == 0) sm.my_rank = -1;
     // Candidate blocks: a range that surely contains every block holding an item of [t0, t0 + n)
     // (block w starts at or after w * base and before (w + 1) * (base + 1))
     const int t0 = sch.t0, members = sch.members;
@@ -522,6 +535,7 @@ __device__ inline void combine_live_from_schedule(LiveList& sm, const TileSchedu
         const unsigned long long mask = __ballot(live);
         const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
         if (live) sm.live[(k & (R - 1)) * stride + (k >> log_r)] = lo - t0;
+        if (live && w == my_block) sm.my_rank = k;
         if (count == 0 && mask != 0) live0 = __builtin_amdgcn_readlane(lo - t0, __builtin_ctzll(mask));
         count += __popcll(mask);
     }
@@ -529,12 +543,21 @@ __device__ inline void combine_live_from_schedule(LiveList& sm, const TileSchedu
 }
 
 struct CombineArgs {
-    const float* plse;      // the tile's lse lines
-    const float* po;        // the tile's o blocks
+    const float* plse;      // lse lines of the rows to merge
+    const float* po;        // their o blocks
     float* out_rows;
     float* lse_rows;        // or null
     int G, n_live, KJ, log_r, stride;
+    bool to_partial;        // the result is itself a partial another workgroup will merge: coherent stores,
+                            // lse left in base-2 units (two-level combine, first level)
 };
+
+// Stores of a combine's result.
+__device__ __forceinline__ void combine_store_o(const CombineArgs& a, int pair, float4 o)
+{
+    if (a.to_partial) store_agent4(a.out_rows + 4 * pair, f32x4{o.x, o.y, o.z, o.w});
+    else reinterpret_cast<float4*>(a.out_rows)[pair] = o;
+}
 
 // Second half of combine_tile: weights, row loop, output.  NR0 = rows in a thread's first batch
 // = min(BATCH, KJ), a template parameter so that every thread issues exactly NL lse loads and then
@@ -625,7 +648,8 @@ __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs&
         const float L = row16_sum(l);
         if (sj == 0) {
             sm.invL[sg] = __builtin_amdgcn_rcpf(L);
-            if (a.lse_rows) a.lse_rows[sg] = (M + fast_log2(L)) * kLn2;
+            if (a.to_partial) store_agent(&a.lse_rows[sg], M + fast_log2(L));
+            else if (a.lse_rows) a.lse_rows[sg] = (M + fast_log2(L)) * kLn2;
         }
     }
     __syncthreads();
@@ -681,19 +705,60 @@ __device__ __forceinline__ void combine_rows(const Params& p, const CombineArgs&
                     const float4 t = sm.red[r * kPairs + pair];
                     o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
                 }
-                reinterpret_cast<float4*>(a.out_rows)[pair] = o;
+                combine_store_o(a, pair, o);
             }
         } else if (active) {
-            reinterpret_cast<float4*>(a.out_rows)[pair] = o;
+            combine_store_o(a, pair, o);
         }
     }
 }
 
-// live_ready: the live list is already in sm (combine_live_from_schedule); otherwise wave 0
-// finds the live slots by reading head 0's lse of every slot.
+// The live rows among n candidates, found by reading head 0's lse of each (a row without a partial
+// holds -inf there).  Wave 0 only (all 64 lanes).
+__device__ __forceinline__ void combine_live_from_memory(LiveList& ll, const float* plse, int n, int G)
+{
+    const int lane = threadIdx.x & 63;
+    const int log_r = combine_log_r(G), R = 1 << log_r, stride = combine_live_stride(log_r);
+    int count = 0, live0 = 0;
+#pragma nounroll
+    for (int base = 0; base < n; base += 256) {          // one trip up to 256 slots
+        float first[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = base + j * 64 + lane;
+            first[j] = load_agent(&plse[min(i, n - 1) * kLseStride]);     // unconditional: the 4 loads fly together
+            if (i >= n) first[j] = -INFINITY;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (base + j * 64 < n) {
+                const bool live = first[j] != -INFINITY;
+                const unsigned long long mask = __ballot(live);
+                const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
+                if (live) ll.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
+                if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
+                count += __popcll(mask);
+            }
+        }
+    }
+    combine_live_finish(ll, count, live0, log_r, lane);
+}
+
+// What a combine merges and where the result goes.
+struct CombineJob {
+    const float* plse;      // lse lines of the candidate rows (row i at plse + i * kLseStride)
+    const float* po;        // their o blocks (row i at po + i * G * kD)
+    float* out_rows;        // [G][kD]
+    float* lse_rows;        // [G] or null (never null with to_partial)
+    int n;                  // candidate rows (slots) to scan when the live list is not there yet
+    bool to_partial;        // see CombineArgs
+};
+
+// live_ready: the live list is already in ll (combine_live_from_schedule, or a caller's own
+// list); otherwise wave 0 finds the live rows by reading head 0's lse of every candidate.
 template <int BATCH>
-__device__ __forceinline__ void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm, LiveList& ll,
-                                    bool live_ready = false)
+__device__ __forceinline__ void combine_core(const Params& p, const CombineJob& job, CombineSmem& sm, LiveList& ll,
+                                             bool live_ready)
 {
     static_assert(BATCH % kCombineGroup == 0 && BATCH <= 32, "row batch");
     const int G = p.G;          // <= 16
@@ -702,41 +767,17 @@ __device__ __forceinline__ void combine_tile(const Params& p, int tile, int b, i
     // occupied during the K/V streaming.
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    const int lane = tid & 63;
-    const float* plse = p.part_lse + (size_t)tile * p.max_splits * kLseStride;
-    const float* po = p.part_o + (size_t)tile * p.max_splits * G * kD;
-    float* out_rows = p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD;
-    float* lse_rows = p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr;
+    const float* plse = job.plse;
+    const float* po = job.po;
+    float* out_rows = job.out_rows;
+    float* lse_rows = job.lse_rows;
+    const int n = job.n;
 
     const int log_r = combine_log_r(G);
     const int R = 1 << log_r;
     const int stride = combine_live_stride(log_r);       // of one slice's live list
 
-    if (tid < 64 && !live_ready) {
-        int count = 0, live0 = 0;
-#pragma nounroll
-        for (int base = 0; base < n; base += 256) {      // one trip up to 256 slots
-            float first[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = base + j * 64 + lane;
-                first[j] = load_agent(&plse[min(i, n - 1) * kLseStride]);     // unconditional: the 4 loads fly together
-                if (i >= n) first[j] = -INFINITY;
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (base + j * 64 < n) {
-                    const bool live = first[j] != -INFINITY;
-                    const unsigned long long mask = __ballot(live);
-                    const int k = count + __popcll(mask & ((1ull << lane) - 1ull));
-                    if (live) ll.live[(k & (R - 1)) * stride + (k >> log_r)] = base + j * 64 + lane;
-                    if (count == 0 && mask != 0) live0 = base + j * 64 + __builtin_ctzll(mask);
-                    count += __popcll(mask);
-                }
-            }
-        }
-        combine_live_finish(ll, count, live0, log_r, lane);
-    }
+    if (tid < 64 && !live_ready) combine_live_from_memory(ll, plse, n, G);
     trace_event(p, kEvCombA);
     __syncthreads();
     const int n_live = ll.n_live;
@@ -756,9 +797,9 @@ __device__ __forceinline__ void combine_tile(const Params& p, int tile, int b, i
         return;
     }
 
-    // the rest is compiled once per number of row groups in a thread's first batch, so that the
+    // the rest is compiled once per number of rows in a thread's first batch, so that the
     // number of row loads between the lse loads and their first use is a compile-time constant
-    const CombineArgs a = {plse, po, out_rows, lse_rows, G, n_live, KJ, log_r, stride};
+    const CombineArgs a = {plse, po, out_rows, lse_rows, G, n_live, KJ, log_r, stride, job.to_partial};
     switch (min(BATCH, KJ)) {
         case 1: combine_rows<BATCH, 1>(p, a, sm, ll, tid); break;
         case 2: combine_rows<BATCH, 2>(p, a, sm, ll, tid); break;
@@ -769,6 +810,125 @@ __device__ __forceinline__ void combine_tile(const Params& p, int tile, int b, i
         default: combine_rows<BATCH, (BATCH >= 32 ? 32 : 8)>(p, a, sm, ll, tid); break;
     }
     __syncthreads();
+}
+
+// The flat combine of tile (b, kvh): its n slots' partials into out / lse.
+template <int BATCH>
+__device__ __forceinline__ void combine_tile(const Params& p, int tile, int b, int kvh, int n, CombineSmem& sm, LiveList& ll,
+                                             bool live_ready = false)
+{
+    const int G = p.G;
+    const CombineJob job = {p.part_lse + (size_t)tile * p.max_splits * kLseStride,
+                            p.part_o + (size_t)tile * p.max_splits * G * kD,
+                            p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD,
+                            p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr,
+                            n, false};
+    combine_core<BATCH>(p, job, sm, ll, live_ready);
+}
+
+// ---- Two-level combine -------------------------------------------------------------------
+// One compute unit pulls partial rows at some 50 GB/s, so a tile with hundreds of partials (one
+// long sequence on one or two KV heads, cut over the whole chip) would spend longer in its
+// combine than in the K/V stream.  Such a tile is merged in two levels, still without anybody
+// waiting: its live partials, in ascending slot order, form groups of kTreeGroup; a group has an
+// arrival counter of its own; the workgroup that completes a group's count merges the group's
+// rows into ONE partial of a second buffer (coherent stores, base-2 lse, like any partial) and
+// then counts the group as arrived at the tile's counter; whoever completes that count merges the
+// groups' results into out / lse.  Groups follow from the schedule alone and every merge takes
+// its rows in ascending order, so the result does not depend on who merges, and the
+// bulk-synchronous kernel 2 (one workgroup per group) computes the same bits.
+
+// Wave 0: the live list becomes its own rows [first, first + count), count <= 64.
+__device__ __forceinline__ void tree_sublist(LiveList& ll, int first, int count, int G)
+{
+    const int lane = threadIdx.x & 63;
+    const int log_r = combine_log_r(G), R = 1 << log_r, stride = combine_live_stride(log_r);
+    const int k = first + lane;
+    // every lane reads its entry before any lane writes (one instruction each, in order)
+    const int slot = lane < count ? ll.live[(k & (R - 1)) * stride + (k >> log_r)] : 0;
+    const int slot0 = __builtin_amdgcn_readfirstlane(slot);
+    if (lane < count) ll.live[(lane & (R - 1)) * stride + (lane >> log_r)] = slot;
+    combine_live_finish(ll, count, slot0, log_r, lane);
+}
+
+// Wave 0: the live list 0, 1, ..., count - 1 (the groups' results, all live).
+__device__ __forceinline__ void tree_identity_list(LiveList& ll, int count, int G)
+{
+    const int lane = threadIdx.x & 63;
+    const int log_r = combine_log_r(G), R = 1 << log_r, stride = combine_live_stride(log_r);
+#pragma nounroll
+    for (int k = lane; k < count; k += 64) ll.live[(k & (R - 1)) * stride + (k >> log_r)] = k;
+    combine_live_finish(ll, count, 0, log_r, lane);
+}
+
+// The whole workgroup: merges first-level group `grp` of tile (b, kvh), whose m > kTreeGroup live
+// partials are listed in ll and all written, counts the group at the tile's counter and, if
+// that completes the tile, merges the groups' results into out / lse.  `flag`: a word of LDS.
+template <int BATCH>
+__device__ __forceinline__ void tree_merge_group(const Params& p, int tile, int b, int kvh, int grp, int m,
+                                                 CombineSmem& sm, LiveList& ll, int* flag)
+{
+    const int G = p.G;
+    const int first = grp * kTreeGroup;
+    const int gsize = min(kTreeGroup, m - first);
+    const int n_groups = (m + kTreeGroup - 1) / kTreeGroup;
+    const size_t base2 = (size_t)tile * p.group_cap;
+    // level 0: the group's rows into the second buffer; level 1 (only for the workgroup that
+    // completes the tile's count of groups): the groups' results into out / lse.  One loop, so
+    // that the combine is compiled into the kernel once for both.
+#pragma nounroll
+    for (int level = 0; level < 2; ++level) {
+        if (threadIdx.x < 64) {
+            if (level == 0) tree_sublist(ll, first, gsize, G);
+            else tree_identity_list(ll, n_groups, G);
+        }
+        CombineJob job;
+        if (level == 0) {
+            job = {p.part_lse + (size_t)tile * p.max_splits * kLseStride, p.part_o + (size_t)tile * p.max_splits * G * kD,
+                   p.part2_o + (base2 + grp) * G * kD, p.part2_lse + (base2 + grp) * kLseStride, 0, true};
+        } else {
+            job = {p.part2_lse + base2 * kLseStride, p.part2_o + base2 * G * kD,
+                   p.out + ((size_t)b * p.Hq + (size_t)kvh * G) * kD,
+                   p.lse ? p.lse + (size_t)b * p.Hq + (size_t)kvh * G : nullptr, 0, false};
+        }
+        combine_core<BATCH>(p, job, sm, ll, true);
+        if (level == 1) {
+            if (threadIdx.x == 0)                               // re-arm for the next call
+                __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+        // the group's result went out with coherent stores: acknowledged, then counted
+        wait_stores_done();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t old = __hip_atomic_fetch_add(&p.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = old + 1u == (uint32_t)n_groups;
+        }
+        __syncthreads();
+        if (!*flag) break;
+    }
+    __syncthreads();
+}
+
+// Fused kernel: this workgroup's partial, number `rank` of the tile's m live ones, is written and
+// acknowledged and the workgroup has passed a barrier.  Counts it at its group; the workgroup
+// that completes the group goes on with tree_merge_group.
+template <int BATCH>
+__device__ __forceinline__ void tree_arrive(const Params& p, int tile, int b, int kvh, int rank, int m,
+                                            CombineSmem& sm, LiveList& ll, int* flag)
+{
+    const int grp = rank / kTreeGroup;
+    const int gsize = min(kTreeGroup, m - grp * kTreeGroup);
+    uint32_t* gc = &p.group_counters[(size_t)tile * kMaxGroups + grp];
+    if (threadIdx.x == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = old + 1u == (uint32_t)gsize;
+        if (last) __hip_atomic_store(gc, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // re-arm for the next call
+        *flag = last;
+    }
+    __syncthreads();
+    if (*flag) tree_merge_group<BATCH>(p, tile, b, kvh, grp, m, sm, ll, flag);
+    else __syncthreads();
 }
 
 }  // namespace fd

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -114,7 +115,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
     // Ask for every line of the argument block at once: left alone, the compiler fetches each
     // field at its first use, three dependent scalar-cache misses in a row (0.25 us each)
     // before the first K/V request can go out.
-    asm volatile("" ::"s"(p.trace), "s"(p.part_o), "s"(p.block_table), "s"(p.num_pages));
+    asm volatile("" ::"s"(p.trace), "s"(p.part_o), "s"(p.block_table), "s"(p.num_pages), "s"(p.tree_rows));
     const int G = p.G;
     const int lane = threadIdx.x & 63;
     const int sl_first = lane < p.B ? p.seq_lens[lane] : 0;     // in flight during the work-list arithmetic
@@ -173,7 +174,10 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
                 if (l && threadIdx.x < G) l[threadIdx.x] = -INFINITY;
             }
             // bulk-synchronous mode: tell kernel 2 that this tile needs no combine
-            if (MODE == kModeBsp && threadIdx.x == 0) p.counters[it.tile] = 1u;
+            if (MODE == kModeBsp && threadIdx.x == 0) {
+                if (p.bsp_groups == 1) p.counters[it.tile] = 1u;
+                else p.bsp_direct[it.tile] = 1u;
+            }
             // fine-grained waits: tell the waiting combine workgroup that there is nothing to merge
             if (MODE == kModeSignal) {
                 __syncthreads();
@@ -191,7 +195,7 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
         const auto list_live = [&] {
             if (MODE == kModeFused) {
                 const TileSchedule sch = {t0, wl.base, wl.rem, wl.members, c, it.S};
-                combine_live_from_schedule(ss.live, sch, it.n, G);
+                combine_live_from_schedule(ss.live, sch, it.n, G, wl.wl);
             }
         };
         if (j0 < j1)
@@ -203,6 +207,9 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             store_agent(&p.part_lse[(slot + r) * kLseStride], -INFINITY);
 
         trace_event(p, kEvPartialOut);
+        // bulk-synchronous mode with several workgroups of kernel 2 per tile: this tile does need
+        // them (every workgroup that holds a part of it says so)
+        if (MODE == kModeBsp && p.bsp_groups > 1 && threadIdx.x == 0) p.bsp_direct[it.tile] = 0u;
         if (MODE != kModeBsp) {
             // a7: the partial went out with coherent stores; once they are acknowledged
             // and every wave has reached the barrier, one thread counts the run's splits
@@ -211,6 +218,17 @@ __device__ __forceinline__ void persistent_loop(const Params& p, const Path& pat
             wait_stores_done();
             trace_event(p, kEvStoresAcked);
             __syncthreads();
+            if (MODE == kModeFused && p.tree_rows != INT32_MAX) {      // (the host rules it out for most launches)
+                // a tile with very many partials is merged in two levels (tree_arrive); a run
+                // without keys holds no partial and is not counted there
+                const int m = __builtin_amdgcn_readfirstlane(ss.live.n_live);
+                if (m > p.tree_rows) {
+                    const int rank = __builtin_amdgcn_readfirstlane(ss.live.my_rank);
+                    if (j0 < j1) tree_arrive<COMB_BATCH>(p, it.tile, it.b, it.kvh, rank, m, comb, ss.live, &ss.is_last);
+                    __syncthreads();
+                    continue;
+                }
+            }
             uint32_t old = 0;
             if (threadIdx.x == 0)
                 old = __hip_atomic_fetch_add(&p.counters[it.tile], (uint32_t)run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -293,6 +311,33 @@ __global__ __launch_bounds__(kWgThreads) void fd_combine_kernel(Params p)
     trace_event(p, kEvStart);
     combine_tile<32>(p, tile, b, kvh, n, sm, ll);
     trace_event(p, kEvEnd);
+}
+
+// Kernel 2 of the bulk-synchronous baseline for launches in which a tile may hold more than
+// p.tree_rows partials: workgroup (x, y) = (tile, first-level group), p.bsp_groups per tile.
+// Workgroup (tile, g) merges group g of a tile that does hold that many (the last of them to finish
+// merges the groups' results), workgroup (tile, 0) merges a tile that does not, and the rest leave.
+// Tiles that kernel 1 wrote as final results are marked in p.bsp_direct, which kernel 1 writes for
+// every tile and nobody clears (several workgroups look at the mark).
+__global__ __launch_bounds__(kWgThreads) void fd_combine_tree_kernel(Params p)
+{
+    __shared__ CombineSmem sm;
+    __shared__ LiveList ll;
+    __shared__ int flag;
+    const int tile = blockIdx.x, grp = blockIdx.y;
+    const int b = tile / p.Hkv, kvh = tile - b * p.Hkv;
+    const uint32_t direct = p.bsp_direct[tile];
+    const int n = num_splits_of(p, seq_len_of(p, b));
+    if (direct) return;
+    if (threadIdx.x < 64) combine_live_from_memory(ll, p.part_lse + (size_t)tile * p.max_splits * kLseStride, n, p.G);
+    __syncthreads();
+    const int m = ll.n_live;
+    __syncthreads();                       // everybody has m before wave 0 rewrites the list
+    if (m > p.tree_rows) {
+        if (grp * kTreeGroup < m) tree_merge_group<32>(p, tile, b, kvh, grp, m, sm, ll, &flag);
+        return;
+    }
+    if (grp == 0) combine_tile<32>(p, tile, b, kvh, n, sm, ll, true);
 }
 
 
@@ -400,7 +445,9 @@ int fail(int code, const char* fmt, ...)
 constexpr uint32_t kMagic = 0x46444831u;
 
 struct Layout {
-    size_t part_o_off, part_lse_off, counters_off, status_off, total;
+    size_t part_o_off, part_lse_off, part2_o_off, part2_lse_off;
+    size_t counters_off, group_counters_off, bsp_direct_off, status_off, total;     // zeroed from counters_off on
+    int group_cap;
 };
 
 }  // namespace
@@ -413,7 +460,7 @@ struct fd_handle_s {
     int num_cus;
     void* workspace;
     Layout lay;
-    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring, opt_spin_limit, opt_split_keys;
+    int opt_path, opt_xcd, opt_wgs_per_cu, opt_ring, opt_spin_limit, opt_split_keys, opt_tree_rows;
     hipStream_t side_stream;      // fine-grained waits: the waiting combine kernel runs here
     hipEvent_t ev_fork, ev_join;
     int last_grid, last_path;
@@ -453,10 +500,17 @@ Layout make_layout(const fd_config& c)
     const size_t tiles = (size_t)c.B * c.Hkv, G = (size_t)(c.Hq / c.Hkv);
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     Layout l;
+    // first-level groups of the two-level combine: a tile has at most max_splits partials
+    l.group_cap = (c.max_splits + fd::kTreeGroup - 1) / fd::kTreeGroup;
+    if (l.group_cap > fd::kMaxGroups) l.group_cap = fd::kMaxGroups;
     l.part_o_off = 0;
     l.part_lse_off = up(tiles * c.max_splits * G * fd::kD * sizeof(float));
-    l.counters_off = l.part_lse_off + up(tiles * c.max_splits * fd::kLseStride * sizeof(float));
-    l.status_off = l.counters_off + up(tiles * sizeof(uint32_t));
+    l.part2_o_off = l.part_lse_off + up(tiles * c.max_splits * fd::kLseStride * sizeof(float));
+    l.part2_lse_off = l.part2_o_off + up(tiles * l.group_cap * G * fd::kD * sizeof(float));
+    l.counters_off = l.part2_lse_off + up(tiles * l.group_cap * fd::kLseStride * sizeof(float));
+    l.group_counters_off = l.counters_off + up(tiles * sizeof(uint32_t));
+    l.bsp_direct_off = l.group_counters_off + up(tiles * fd::kMaxGroups * sizeof(uint32_t));
+    l.status_off = l.bsp_direct_off + up(tiles * sizeof(uint32_t));
     l.total = l.status_off + 256;
     return l;
 }
@@ -487,9 +541,13 @@ int launch_fill(void* dst, size_t bytes, uint32_t value, hipStream_t st)
     return FD_OK;
 }
 
+// p.bsp_groups workgroups per tile: 1, or the first-level groups a tile of this launch may have
 int launch_combine(const fd::Params& p, hipStream_t st)
 {
-    hipLaunchKernelGGL(fd::fd_combine_kernel, dim3(p.B * p.Hkv), dim3(fd::kWgThreads), 0, st, p);
+    if (p.bsp_groups > 1)
+        hipLaunchKernelGGL(fd::fd_combine_tree_kernel, dim3(p.B * p.Hkv, p.bsp_groups), dim3(fd::kWgThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL(fd::fd_combine_kernel, dim3(p.B * p.Hkv), dim3(fd::kWgThreads), 0, st, p);
     FD_HIP(hipGetLastError());
     return FD_OK;
 }
@@ -697,6 +755,31 @@ int decode_common(fd_handle_t h, const void* q, const void* k, const void* v, co
     p.part_lse = (float*)(ws + h->lay.part_lse_off);
     p.counters = (uint32_t*)(ws + h->lay.counters_off);
     p.status = (uint32_t*)(ws + h->lay.status_off);
+    p.part2_o = (float*)(ws + h->lay.part2_o_off);
+    p.part2_lse = (float*)(ws + h->lay.part2_lse_off);
+    p.group_counters = (uint32_t*)(ws + h->lay.group_counters_off);
+    p.bsp_direct = (uint32_t*)(ws + h->lay.bsp_direct_off);
+    p.group_cap = h->lay.group_cap;
+    // Two-level combine: only where a tile can hold more partials than the threshold.  A tile's
+    // partials are at most its splits, at most the workgroups of its list, and, with a fixed split
+    // count, about one per block of items that overlaps it.
+    {
+        const int tree_rows = h->opt_tree_rows > 0 ? h->opt_tree_rows : fd::kTreeRowsDefault;
+        const long long n_eff = n_splits > 0 ? n_splits : c.max_splits;
+        const long long members = (grid + X - 1) / X;
+        long long rows_bound = n_eff < members ? n_eff : members;
+        if (n_splits > 0 && tiles / X > 0) {
+            const long long base = (long long)(tiles / X) * n_splits / members;     // items per block (the shortest list)
+            if (base >= 1 && n_splits / base + 2 < rows_bound) rows_bound = n_splits / base + 2;
+        }
+        const bool tree = mode != fd::kModeSignal && rows_bound > tree_rows;
+        p.tree_rows = tree ? tree_rows : INT32_MAX;
+        p.bsp_groups = 1;
+        if (tree) {
+            p.bsp_groups = (int)((rows_bound + fd::kTreeGroup - 1) / fd::kTreeGroup);
+            if (p.bsp_groups > h->lay.group_cap) p.bsp_groups = h->lay.group_cap;
+        }
+    }
     p.spin_limit = h->opt_spin_limit > 0 ? (uint32_t)h->opt_spin_limit : (1u << 20);
     p.B = c.B; p.Hq = c.Hq; p.Hkv = c.Hkv; p.G = h->G; p.S_max = c.S_max;
     p.n_splits = n_splits;
@@ -836,7 +919,7 @@ int fd_create(const fd_config* cfg, fd_handle_t* out)
     h->device = dev;
     h->num_cus = prop.multiProcessorCount;
     h->lay = make_layout(*cfg);
-    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = h->opt_spin_limit = h->opt_split_keys = 0;
+    h->opt_path = h->opt_xcd = h->opt_wgs_per_cu = h->opt_ring = h->opt_spin_limit = h->opt_split_keys = h->opt_tree_rows = 0;
     h->side_stream = nullptr;
     h->ev_fork = h->ev_join = nullptr;
     h->last_grid = h->last_path = 0;
@@ -1105,6 +1188,10 @@ int fd_set_option(fd_handle_t h, int32_t key, int32_t value)
             if (value != 0 && (value < 2 || value > 4)) return fail(FD_ERR_INVALID_ARG, "FD_OPT_RING_STAGES must be 0, 2, 3 or 4");
             h->opt_ring = value;
             return FD_OK;
+        case FD_OPT_TREE_ROWS:
+            if (value < 0 || (value > 0 && value < 2)) return fail(FD_ERR_INVALID_ARG, "FD_OPT_TREE_ROWS must be 0 or at least 2");
+            h->opt_tree_rows = value;
+            return FD_OK;
         case FD_OPT_SPLIT_KEYS:
             if (value != 0 && (value < fd::kSplitAlign || value > 65536 || value % fd::kSplitAlign))
                 return fail(FD_ERR_INVALID_ARG, "FD_OPT_SPLIT_KEYS must be 0 or a multiple of %d in %d..65536", fd::kSplitAlign, fd::kSplitAlign);
@@ -1127,6 +1214,7 @@ int fd_get_option(fd_handle_t h, int32_t key, int32_t* value)
         case FD_OPT_RING_STAGES: *value = h->opt_ring; return FD_OK;
         case FD_OPT_SPIN_LIMIT: *value = h->opt_spin_limit; return FD_OK;
         case FD_OPT_SPLIT_KEYS: *value = h->opt_split_keys; return FD_OK;
+        case FD_OPT_TREE_ROWS: *value = h->opt_tree_rows; return FD_OK;
         case FD_INFO_WAIT_GAVE_UP: {
             uint32_t flag = 0;
             FD_HIP(hipDeviceSynchronize());

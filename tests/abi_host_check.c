@@ -43,10 +43,13 @@ int main(void)
     CHECK(fd_version() == FD_VERSION);
     CHECK(strcmp(fd_last_error(), "") == 0);
 
-    /* workspace formula: partials, one 128-byte line of LSEs per slot, counters and status word, each rounded up to 256 bytes */
+    /* workspace formula: partials, one 128-byte line of LSEs per slot; second-level partials (one group of 16
+     * splits here) and their LSE lines; tile counters, 64 group counters per tile, direct marks and the status
+     * word, each array rounded up to 256 bytes */
     fd_config c = good();
-    const size_t tiles = 4, G = 4, n = 16;
-    CHECK(fd_workspace_bytes(&c) == tiles * n * G * 128 * 4 + tiles * n * 128 + 256 + 256);
+    const size_t tiles = 4, G = 4, n = 16, groups = 1;
+    CHECK(fd_workspace_bytes(&c) == tiles * n * G * 128 * 4 + tiles * n * 128 + tiles * groups * G * 128 * 4 +
+                                        tiles * groups * 128 + 256 + tiles * 64 * 4 + 256 + 256);
     CHECK(fd_workspace_bytes(NULL) == 0);
 
     /* configurations that must be refused, by fd_workspace_bytes, fd_create and fd_decode_static alike */

@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_is_built_and_loads():
     assert os.path.exists(fd.LIB_PATH), "run `python -m paper_2511_02168_amd.build` first"
-    assert fd.fd_version() == 140
+    assert fd.fd_version() == 150
 
 
 def test_every_declared_symbol_is_exported():
@@ -41,7 +41,10 @@ def good_cfg(**kw):
 def test_workspace_bytes_formula():
     cfg = good_cfg()
     tiles, G, n = 4, 4, 16
-    expect = tiles * n * G * 128 * 4 + tiles * n * 128 + 256 + 256   # partials, one 128-byte line of LSEs per slot, counters, status word (256-byte rounded)
+    groups = 1                                                        # ceil(16 splits / 16 partials per first-level group)
+    expect = (tiles * n * G * 128 * 4 + tiles * n * 128                # partials, one 128-byte line of LSEs per slot
+              + tiles * groups * G * 128 * 4 + tiles * groups * 128    # second-level partials and their LSE lines
+              + 256 + tiles * 64 * 4 + 256 + 256)                      # tile counters, 64 group counters per tile, direct marks, status word
     assert fd.fd_workspace_bytes(cfg) == expect
     assert fd.fd_workspace_bytes(good_cfg(D=64)) == 0
 
