@@ -48,7 +48,8 @@ enum {
     FD_ERR_HIP = -4          /* a HIP runtime call failed (no device, launch error)          */
 };
 
-/* Keys per split used when the library picks the split count itself (FD_OPT_SPLIT_KEYS = 0). */
+/* Keys per split used when the library picks the split count itself (FD_OPT_SPLIT_KEYS = 0); half
+ * of it for shapes with very few items, see fd_decode. */
 #define FD_ADAPTIVE_SPLIT_KEYS 512
 /* Upper bound accepted for fd_config.max_splits. */
 #define FD_MAX_SPLITS 1024
@@ -149,7 +150,9 @@ int fd_reset(fd_handle_t h, void* stream);
  *                 n_splits <= max_splits.
  *            = 0: adaptive, n_b = clamp(ceil(seq_lens[b]/512), 1, max_splits) ranges of
  *                 the sequence's own length, computed on the device (FD_OPT_SPLIT_KEYS
- *                 replaces the 512).
+ *                 replaces the 512; left at 0, the library takes 256 instead when even
+ *                 B*Hkv sequences of S_max keys would give no more items than a quarter
+ *                 of the GPU's compute units).
  *   stream   hipStream_t (NULL = default stream)
  *
  * seq_lens[b] == 0 gives out = 0 and lse = -inf for that sequence.
@@ -286,7 +289,7 @@ int fd_autotune(fd_handle_t h, const void* q, const void* k_cache, const void* v
  *                        long sequence on one or two KV heads).  0 auto (64), else >= 2.
  *                        fd_decode and fd_decode_bsp agree bitwise for any value; fd_decode_waits
  *                        always merges in one level and then differs from them in rounding
- *   FD_OPT_SPLIT_KEYS    n_splits = 0: keys per split the split count is derived from (0 = 512;
+ *   FD_OPT_SPLIT_KEYS    n_splits = 0: keys per split the split count is derived from (0 = 512, or 256 for very few items, see fd_decode;
  *                        else a multiple of 64 in 64..65536)
  *   FD_INFO_*            read-only, through fd_get_option; FD_INFO_WAIT_GAVE_UP synchronises the device
  */
