@@ -924,3 +924,33 @@ def test_calls_recorded_into_a_hip_graph_replay_like_eager_calls():
         o64, l64 = oracle.decode(fi.bits(q), fi.bits(inp.k), fi.bits(inp.v), sl.cpu().numpy())
         check_out(outs["fused"].cpu().numpy(), o64, "graph replay")
         check_lse(lses["fused"].cpu().numpy(), l64, "graph replay")
+
+
+def test_two_handles_on_two_streams_at_once():
+    """Two persistent launches share the GPU: neither fits beside the other completely, so workgroups of one
+    start only as workgroups of the other leave.  No workgroup ever waits for another (the last arriver
+    combines), so both finish, and each call's result is that of the call run alone, bit for bit."""
+    wa = fi.Workload("conc_a", 8201, B=8, Hq=32, Hkv=8, S_max=4096, n_splits=16)
+    wb = fi.Workload("conc_b", 8202, B=1, Hq=8, Hkv=1, S_max=16384, n_splits=256)      # two-level combine
+    say("case two handles, two streams, 200 overlapping calls each")
+    ia, ib = fi.make_inputs(wa, "cuda"), fi.make_inputs(wb, "cuda")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    with fd.FlashDecode(wa.B, wa.Hq, wa.Hkv, wa.S_max, max_splits=16) as da, \
+            fd.FlashDecode(wb.B, wb.Hq, wb.Hkv, wb.S_max, max_splits=256) as db:
+        alone_a = da.decode(ia.q, ia.k, ia.v, ia.seq_lens, 16)
+        alone_b = db.decode(ib.q, ib.k, ib.v, ib.seq_lens, 256)
+        torch.cuda.synchronize()
+        outs_a = [torch.empty_like(alone_a[0]) for _ in range(4)]
+        outs_b = [torch.empty_like(alone_b[0]) for _ in range(4)]
+        lse_a, lse_b = torch.empty_like(alone_a[1]), torch.empty_like(alone_b[1])
+        for i in range(200):
+            bsp = i % 3 == 2
+            da.decode(ia.q, ia.k, ia.v, ia.seq_lens, 16, out=outs_a[i % 4], lse=lse_a, bsp=bsp, stream=sa.cuda_stream)
+            db.decode(ib.q, ib.k, ib.v, ib.seq_lens, 256, out=outs_b[i % 4], lse=lse_b, bsp=bsp, stream=sb.cuda_stream)
+        torch.cuda.synchronize()
+        for o in outs_a:
+            assert torch.equal(o.view(torch.int32), alone_a[0].view(torch.int32)), "stream A: result differs from the call run alone"
+        for o in outs_b:
+            assert torch.equal(o.view(torch.int32), alone_b[0].view(torch.int32)), "stream B: result differs from the call run alone"
+        assert all(c == 0 for c in fd.fd_debug_read_counters(da.h, wa.B * wa.Hkv))
+        assert all(c == 0 for c in fd.fd_debug_read_counters(db.h, wb.B * wb.Hkv))
