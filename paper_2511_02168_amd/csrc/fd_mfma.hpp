@@ -375,6 +375,11 @@ __device__ __forceinline__ void mfma_item(const Params& p, int b, int kvh, int j
         // NST - 1 stages go out up front (measured: requesting the whole ring at once and
         // waiting for all of it starts the first consume later and loses half a microsecond)
         for (int s = (c0 == 0 ? n_requested : 0); s < P && s < cmine; ++s) issue(s);
+        // The caller's side job (LDS and arithmetic only), once, by wave 0, with its first requests
+        // on their way and BEFORE the compiler's wait for q below: that wait is "every vector load
+        // of this wave has returned", the stage requests included, so whatever stands behind it
+        // runs after the first stage has landed instead of beside its flight.
+        if (c0 == 0 && wave == 0) hook();
         // Make the compiler wait for the q loads HERE: the loop below must contain no
         // compiler-generated vmcnt wait, which would also drain the stage loads the loop
         // keeps in flight (they are issued from inline asm, invisible to its counter).
@@ -385,16 +390,12 @@ __device__ __forceinline__ void mfma_item(const Params& p, int b, int kvh, int j
         const int full = kb_last + kMfBlockKeys <= j1 ? cmine : cmine - 1;
         for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
-            // the caller's side job, once, by wave 0, right after a request has gone out: the
-            // wave has time to spare then
-            if (c0 + s == 0 && wave == 0) hook();
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kMfBlockKeys;
             mfma_consume_stage<false, F16>(my_ring + (s % NST) * kMfStageBytes, qb, st, sl2, kb, j1, lane);
         }
         if (full < cmine) {
-            if (c0 + full == 0 && wave == 0) hook();
             wait_stages_in_flight(0);
             if (c0 + full == 0) trace_event(p, kEvFirstStage);
             mfma_consume_stage<true, F16>(my_ring + (full % NST) * kMfStageBytes, qb, st, sl2, kb_last, j1, lane);

@@ -273,23 +273,20 @@ __device__ __forceinline__ void mfma8_item(const Params& p, int b, int kvh, int 
         // NST - 1 stages go out up front (measured: requesting the whole ring at once and
         // waiting for all of it starts the first consume later and loses half a microsecond)
         for (int s = (c0 == 0 ? n_requested : 0); s < P && s < cmine; ++s) issue(s);
-        // the compiler's wait for the q loads goes here, outside the loop (see mfma_item)
+        // the caller's side job before, the compiler's wait for the q loads here, outside the loop (see mfma_item)
+        if (c0 == 0 && wave == 0) hook();
         asm volatile("" ::"v"(qb[0]), "v"(qb[1]), "v"(qb[2]), "v"(qb[3]));
         // the range's last block, if ragged, after the loop (see mfma_item)
         const int kb_last = j0 + (wave + kWaves * (c0 + cmine - 1)) * kM8BlockKeys;
         const int full = kb_last + kM8BlockKeys <= j1 ? cmine : cmine - 1;
         for (int s = 0; s < full; ++s) {
             if (s + P < cmine) issue(s + P);
-            // the caller's side job, once, by wave 0, right after a request has gone out: the
-            // wave has time to spare then
-            if (c0 + s == 0 && wave == 0) hook();
             wait_stages_in_flight(min(P, cmine - 1 - s));
             if (c0 + s == 0) trace_event(p, kEvFirstStage);
             const int kb = j0 + (wave + kWaves * (c0 + s)) * kM8BlockKeys;
             mfma8_consume_stage<false>(my_ring + (s % NST) * kMfStageBytes, qb, st, sl2, kb, j1, lane);
         }
         if (full < cmine) {
-            if (c0 + full == 0 && wave == 0) hook();
             wait_stages_in_flight(0);
             if (c0 + full == 0) trace_event(p, kEvFirstStage);
             mfma8_consume_stage<true>(my_ring + (full % NST) * kMfStageBytes, qb, st, sl2, kb_last, j1, lane);

@@ -1,6 +1,7 @@
 """In-kernel timeline of one fused (or split) Flash Decode call: where the microseconds of a call go.
 
     python -m paper_2511_02168_amd.timeline --config c2 [--dtype fp8kv] [--bsp] [--xcd-groups 8]
+    python -m paper_2511_02168_amd.timeline --shape 1 96 8 16384 32      (B Hq Hkv S n_splits, full-length sequences)
 
 Attaches a trace buffer (fd_debug_set_trace), runs a few calls of the workload and prints, for the
 last of them, the spread over the workgroups of every milestone a workgroup stamps with the 100 MHz
@@ -25,13 +26,19 @@ EVENTS = ["start", "first_stage", "loop_end", "partial_out", "stores_acked", "co
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", default="c5")
+    ap.add_argument("--shape", type=int, nargs=5, metavar=("B", "HQ", "HKV", "S", "N_SPLITS"),
+                    help="an ad-hoc workload instead of --config (seeded N(0,1) inputs, every sequence S keys long)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16", "fp8kv"])
     ap.add_argument("--bsp", action="store_true", help="trace fd_decode_bsp (kernel 1's workgroups, then kernel 2's)")
     ap.add_argument("--xcd-groups", type=int, default=0)
     ap.add_argument("--calls", type=int, default=3, help="traced calls (the last one is reported)")
     args = ap.parse_args()
 
-    wl = fi.workload(args.config)
+    if args.shape:
+        B, Hq, Hkv, S, n = args.shape
+        wl = fi.Workload(f"shape_b{B}_hq{Hq}_hkv{Hkv}_s{S}_n{n}", 4242, B=B, Hq=Hq, Hkv=Hkv, S_max=S, n_splits=n)
+    else:
+        wl = fi.workload(args.config)
     inp = fi.make_inputs(wl, "cuda", dtype=torch.float16 if args.dtype == "fp16" else torch.bfloat16)
     fp8 = args.dtype == "fp8kv"
     if fp8:
