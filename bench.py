@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--no-bsp", action="store_true")
     ap.add_argument("--no-waits", action="store_true", help="skip the fine-grained-waits variant (fd_decode_waits)")
     ap.add_argument("--no-hot", action="store_true", help="skip the hot-cache figure (one K/V copy) of the workloads that fit the Infinity Cache")
+    ap.add_argument("--print-sources-digest", action="store_true", help="print the digest of the kernel sources that a profile summary records, and exit")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same calls")
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only streaming kernel (achievable bandwidth)")
     ap.add_argument("--xcd-groups", type=int, default=0)
@@ -147,18 +148,31 @@ def streaming_probe(fd, torch, stream):
 
 def read_traffic(workload_name, dtype, page_size):
     """HBM bytes per launch of the fused kernel from the committed rocprofv3 --pmc summary of THIS workload, element
-    type and cache layout, or None if there is none.  Warns when the summary is older than the kernel sources."""
+    type and cache layout, or None if there is none.  Warns when the summary was measured on other kernel sources."""
     tag = ("" if dtype == "bf16" else f"_{dtype}") + (f"_page{page_size}" if page_size else "")
     path = os.path.join(ROOT, "profiles", f"fd_fused{tag}_{workload_name}_pmc.txt")
     if not os.path.exists(path):
         return None
-    csrc = os.path.join(ROOT, "paper_2511_02168_amd", "csrc")
-    newest = max(os.path.getmtime(os.path.join(csrc, f)) for f in os.listdir(csrc))
-    if os.path.getmtime(path) < newest:
-        print(f"bench.py: warning: {os.path.relpath(path, ROOT)} is older than the kernel sources; "
+    text = open(path).read()
+    # the summary names the kernel sources it was measured on (a digest of their contents); file
+    # times say nothing after a checkout
+    rec = re.search(r"^kernel_sources_sha256\s*=\s*([0-9a-f]+)", text, re.M)
+    if rec is None or rec.group(1) != kernel_sources_digest():
+        print(f"bench.py: warning: {os.path.relpath(path, ROOT)} was not measured on the current kernel sources; "
               "roofline.traffic may be stale", file=sys.stderr)
-    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", text, re.M)
     return float(m.group(1)) if m else None
+
+
+def kernel_sources_digest():
+    """sha256 over the kernel sources (names and contents, in name order), first 16 hex digits."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2511_02168_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def cpu_baseline(inp, wl, fi, fmt="bf16", n_threads=0, seconds=10.0):
@@ -192,6 +206,9 @@ def cpu_baseline(inp, wl, fi, fmt="bf16", n_threads=0, seconds=10.0):
 
 def main():
     args = parse_args()
+    if args.print_sources_digest:
+        print(kernel_sources_digest())
+        return
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X's share of the work); run with --gpus 1",
               file=sys.stderr)
